@@ -1,0 +1,135 @@
+"""ctypes access to ``libkt_oracle.so`` (test infrastructure, see package doc)."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kt_oracle.c")
+_LIB = os.path.join(_HERE, "libkt_oracle.so")
+_lib = None
+
+
+def build_oracle(force=False):
+    """Compile kt_oracle.c with gcc (no fast-math, no FMA contraction)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+           "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build_oracle()
+    lib = ctypes.CDLL(_LIB)
+    dp = ctypes.POINTER(ctypes.c_double)
+    fp = ctypes.POINTER(ctypes.c_float)
+    i8p = ctypes.POINTER(ctypes.c_int8)
+    i64 = ctypes.c_int64
+    lib.kto_num_threads.restype = ctypes.c_int
+    lib.kto_rotate.argtypes = [dp, dp, i64, i64, dp]
+    lib.kto_rotate.restype = None
+    lib.kto_row_moments.argtypes = [dp, i64, dp]
+    lib.kto_row_moments.restype = ctypes.c_int
+    lib.kto_loss_grad.argtypes = [dp, dp, i64, i64, ctypes.c_double, dp, dp, dp, dp]
+    lib.kto_loss_grad.restype = None
+    lib.kto_cayley_step.argtypes = [dp, dp, i64, ctypes.c_double, dp, dp]
+    lib.kto_cayley_step.restype = ctypes.c_int
+    lib.kto_cayley_step_right.argtypes = [dp, dp, i64, ctypes.c_double, dp]
+    lib.kto_cayley_step_right.restype = ctypes.c_int
+    lib.kto_fakequant_int4.argtypes = [dp, dp, i64, i64, ctypes.c_float, fp, fp, i8p, dp]
+    lib.kto_fakequant_int4.restype = None
+    _lib = lib
+    return lib
+
+
+def _d(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _p(a, ct=ctypes.c_double):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def num_threads():
+    return int(_load().kto_num_threads())
+
+
+def rotate(X, R):
+    X, R = _d(X), _d(R)
+    n, d = X.shape
+    assert R.shape == (d, d)
+    Y = np.empty((n, d), dtype=np.float64)
+    _load().kto_rotate(_p(X), _p(R), n, d, _p(Y))
+    return Y
+
+
+def row_moments(y):
+    """Returns (mu, m2, m3, m4, kappa, degenerate) of one row."""
+    y = _d(y).ravel()
+    out = np.empty(5, dtype=np.float64)
+    deg = _load().kto_row_moments(_p(y), y.size, _p(out))
+    return (*out.tolist(), bool(deg))
+
+
+def loss_grad(X, R, kappa_target=0.0, want_G=False, want_dR=True):
+    """Returns dict(loss, row_kurt, dR[, G]) for Y = X R."""
+    X, R = _d(X), _d(R)
+    n, d = X.shape
+    assert R.shape == (d, d)
+    loss = np.zeros(1, dtype=np.float64)
+    rk = np.empty(n, dtype=np.float64)
+    G = np.empty((n, d), dtype=np.float64) if want_G else None
+    dR = np.empty((d, d), dtype=np.float64) if want_dR else None
+    _load().kto_loss_grad(_p(X), _p(R), n, d, float(kappa_target), _p(loss), _p(rk),
+                          _p(G), _p(dR))
+    out = {"loss": float(loss[0]), "row_kurt": rk, "dR": dR}
+    if want_G:
+        out["G"] = G
+    return out
+
+
+def cayley_step(R, G, lr, want_A=False):
+    R, G = _d(R), _d(G)
+    d = R.shape[0]
+    assert R.shape == (d, d) and G.shape == (d, d)
+    out = np.empty((d, d), dtype=np.float64)
+    A = np.empty((d, d), dtype=np.float64) if want_A else None
+    rc = _load().kto_cayley_step(_p(R), _p(G), d, float(lr), _p(out), _p(A))
+    if rc != 0:
+        raise ArithmeticError("singular system in Cayley step")
+    return (out, A) if want_A else out
+
+
+def cayley_step_right(R, G, lr):
+    R, G = _d(R), _d(G)
+    d = R.shape[0]
+    out = np.empty((d, d), dtype=np.float64)
+    rc = _load().kto_cayley_step_right(_p(R), _p(G), d, float(lr), _p(out))
+    if rc != 0:
+        raise ArithmeticError("singular system in Cayley step")
+    return out
+
+
+def fakequant_int4(X, R, clip=1.0, scales_in=None):
+    """Returns dict(scales float32[n], codes int8[n][d], err float64[n][2])."""
+    X, R = _d(X), _d(R)
+    n, d = X.shape
+    assert R.shape == (d, d)
+    sin = None
+    if scales_in is not None:
+        sin = np.ascontiguousarray(np.asarray(scales_in, dtype=np.float32))
+        assert sin.shape == (n,)
+    sout = np.empty(n, dtype=np.float32)
+    codes = np.empty((n, d), dtype=np.int8)
+    err = np.empty((n, 2), dtype=np.float64)
+    _load().kto_fakequant_int4(_p(X), _p(R), n, d, float(clip), _p(sin, ctypes.c_float),
+                               _p(sout, ctypes.c_float), _p(codes, ctypes.c_int8), _p(err))
+    return {"scales": sout, "codes": codes, "err": err}

@@ -1,0 +1,347 @@
+/*
+ * kt_oracle.c -- plain fp64 CPU oracle for the KurTail rotation-learning step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing on the product path may call into this
+ * file; it exists so that the HIP kernels can be checked against an obviously
+ * correct, slow implementation that shares no code with them.
+ *
+ * Every function writes out a definition from the paper (arXiv 2503.01483)
+ * with plain loops, in double precision, two-pass where a mean is involved,
+ * with no blocking, fusion or raw-moment shortcuts:
+ *
+ *   kto_rotate          Y = X R            ("Learning the Rotations": the
+ *                                           linear layer of the small network)
+ *   kto_row_moments     mu, m2, m3, m4, kappa of one row
+ *                                          (Background, "Kurtosis", Eq. 3:
+ *                                           population moments about the mean,
+ *                                           not excess)
+ *   kto_loss_grad       loss = mean_i f(kappa_i), dL/dR = X^T (dL/dY)
+ *                                          (kurtosis loss of Sec. 2 in its
+ *                                           per-token-row reading; gradient by
+ *                                           the chain rule through Eq. 3)
+ *   kto_cayley_step     R+ = (I + lr/2 A)^-1 (I - lr/2 A) R,  A = G R^T - R G^T
+ *                                          ("Optimization in the Orthogonal
+ *                                           Space": Cayley SGD on the Stiefel
+ *                                           manifold; exact solve by LU with
+ *                                           partial pivoting)
+ *   kto_cayley_step_right  the same retraction written on the right of R
+ *   kto_fakequant_int4  per-token symmetric 4-bit fake quantisation of X R
+ *                                          (Background, "Uniform Quantization
+ *                                           for k-bit Precision": b = 0,
+ *                                           s = max|x| / (2^(k-1) - 1); MSE of
+ *                                           Eq. 1; Setup: one scale per row)
+ *
+ * Degenerate rows (no spread: m2 <= 1e-30 * mean(y^2), or an all-zero row):
+ * kappa := 0, gradient row := 0, the row still counts in the 1/n.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py against
+ * closed forms, brute force and library routines it does not itself use.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int kto_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Y[n][d] = X[n][d] * R[d][d], all row-major doubles. */
+void kto_rotate(const double *X, const double *R, int64_t n, int64_t d, double *Y) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) {
+    double *y = Y + i * d;
+    for (int64_t j = 0; j < d; ++j) y[j] = 0.0;
+    for (int64_t k = 0; k < d; ++k) {
+      const double x = X[i * d + k];
+      const double *r = R + k * d;
+      for (int64_t j = 0; j < d; ++j) y[j] += x * r[j];
+    }
+  }
+}
+
+/* Moments of one row about its mean (Eq. 3).  out = {mu, m2, m3, m4, kappa}.
+ * Returns 1 if the row is degenerate (kappa set to 0). */
+int kto_row_moments(const double *y, int64_t d, double out[5]) {
+  double s = 0.0, raw2 = 0.0;
+  for (int64_t j = 0; j < d; ++j) { s += y[j]; raw2 += y[j] * y[j]; }
+  const double mu = s / (double)d;
+  double m2 = 0.0, m3 = 0.0, m4 = 0.0;
+  for (int64_t j = 0; j < d; ++j) {
+    const double c = y[j] - mu;
+    const double c2 = c * c;
+    m2 += c2; m3 += c2 * c; m4 += c2 * c2;
+  }
+  m2 /= (double)d; m3 /= (double)d; m4 /= (double)d; raw2 /= (double)d;
+  out[0] = mu; out[1] = m2; out[2] = m3; out[3] = m4;
+  if (!(m2 > 1e-30 * raw2)) { out[4] = 0.0; return 1; }
+  out[4] = m4 / (m2 * m2);
+  return 0;
+}
+
+static double sgn(double v) { return (v > 0.0) - (v < 0.0); }
+
+/*
+ * loss = (1/n) sum_i f(kappa_i), f(k) = k if kappa_target == 0 else |k - kappa_target|.
+ * dL/dy_ij = s_i * 4/(n d m2_i^2) * [c_ij^3 - m3_i - kappa_i m2_i c_ij],
+ *   s_i = 1 (or sign(kappa_i - kappa_target)); dR = X^T (dL/dY).
+ * row_kurt (n), G (n*d) and dR (d*d) may each be NULL.
+ */
+void kto_loss_grad(const double *X, const double *R, int64_t n, int64_t d,
+                   double kappa_target, double *loss, double *row_kurt,
+                   double *G, double *dR) {
+  double *Y = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
+  double *Gl = G;
+  if (dR && !Gl) Gl = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
+  double *kap = (double *)malloc(sizeof(double) * (size_t)n);
+  kto_rotate(X, R, n, d, Y);
+
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) {
+    double mo[5];
+    const double *y = Y + i * d;
+    const int degenerate = kto_row_moments(y, d, mo);
+    kap[i] = mo[4];
+    if (Gl) {
+      double *g = Gl + i * d;
+      if (degenerate) {
+        for (int64_t j = 0; j < d; ++j) g[j] = 0.0;
+      } else {
+        const double mu = mo[0], m2 = mo[1], m3 = mo[2], kappa = mo[4];
+        const double si = (kappa_target == 0.0) ? 1.0 : sgn(kappa - kappa_target);
+        const double a = si * 4.0 / ((double)n * (double)d * m2 * m2);
+        for (int64_t j = 0; j < d; ++j) {
+          const double c = y[j] - mu;
+          g[j] = a * (c * c * c - m3 - kappa * m2 * c);
+        }
+      }
+    }
+  }
+
+  double acc = 0.0;
+  for (int64_t i = 0; i < n; ++i)
+    acc += (kappa_target == 0.0) ? kap[i] : fabs(kap[i] - kappa_target);
+  if (loss) *loss = acc / (double)n;
+  if (row_kurt) memcpy(row_kurt, kap, sizeof(double) * (size_t)n);
+
+  if (dR) {
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < d; ++k) {
+      double *o = dR + k * d;
+      for (int64_t j = 0; j < d; ++j) o[j] = 0.0;
+      for (int64_t i = 0; i < n; ++i) {
+        const double x = X[i * d + k];
+        const double *g = Gl + i * d;
+        for (int64_t j = 0; j < d; ++j) o[j] += x * g[j];
+      }
+    }
+  }
+  free(Y);
+  free(kap);
+  if (Gl && Gl != G) free(Gl);
+}
+
+/* C[d][d] = A[d][d] * B[d][d]^T */
+static void mat_abt(const double *A, const double *B, int64_t d, double *C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) {
+      double s = 0.0;
+      for (int64_t k = 0; k < d; ++k) s += A[i * d + k] * B[j * d + k];
+      C[i * d + j] = s;
+    }
+}
+
+/* C[d][d] = A[d][d] * B[d][d] */
+static void mat_ab(const double *A, const double *B, int64_t d, double *C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < d; ++i) {
+    double *c = C + i * d;
+    for (int64_t j = 0; j < d; ++j) c[j] = 0.0;
+    for (int64_t k = 0; k < d; ++k) {
+      const double a = A[i * d + k];
+      const double *b = B + k * d;
+      for (int64_t j = 0; j < d; ++j) c[j] += a * b[j];
+    }
+  }
+}
+
+/* C[d][d] = A[d][d]^T * B[d][d] */
+static void mat_atb(const double *A, const double *B, int64_t d, double *C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < d; ++i) {
+    double *c = C + i * d;
+    for (int64_t j = 0; j < d; ++j) c[j] = 0.0;
+    for (int64_t k = 0; k < d; ++k) {
+      const double a = A[k * d + i];
+      const double *b = B + k * d;
+      for (int64_t j = 0; j < d; ++j) c[j] += a * b[j];
+    }
+  }
+}
+
+/*
+ * Solve M Z = B in place (Z overwrites B) by Gaussian elimination with partial
+ * pivoting.  M (d x d) is destroyed.  B has nrhs columns, row-major.
+ * Returns 0, or -1 if a pivot is exactly zero.
+ */
+static int lu_solve(double *M, double *B, int64_t d, int64_t nrhs) {
+  for (int64_t c = 0; c < d; ++c) {
+    int64_t p = c;
+    double best = fabs(M[c * d + c]);
+    for (int64_t r = c + 1; r < d; ++r) {
+      const double v = fabs(M[r * d + c]);
+      if (v > best) { best = v; p = r; }
+    }
+    if (best == 0.0) return -1;
+    if (p != c) {
+      for (int64_t j = 0; j < d; ++j) { double t = M[c * d + j]; M[c * d + j] = M[p * d + j]; M[p * d + j] = t; }
+      for (int64_t j = 0; j < nrhs; ++j) { double t = B[c * nrhs + j]; B[c * nrhs + j] = B[p * nrhs + j]; B[p * nrhs + j] = t; }
+    }
+    const double piv = M[c * d + c];
+#pragma omp parallel for schedule(static)
+    for (int64_t r = c + 1; r < d; ++r) {
+      const double f = M[r * d + c] / piv;
+      if (f != 0.0) {
+        for (int64_t j = c + 1; j < d; ++j) M[r * d + j] -= f * M[c * d + j];
+        for (int64_t j = 0; j < nrhs; ++j) B[r * nrhs + j] -= f * B[c * nrhs + j];
+      }
+      M[r * d + c] = 0.0;
+    }
+  }
+  for (int64_t c = d - 1; c >= 0; --c) {
+    const double piv = M[c * d + c];
+    for (int64_t j = 0; j < nrhs; ++j) B[c * nrhs + j] /= piv;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < c; ++r) {
+      const double f = M[r * d + c];
+      if (f != 0.0)
+        for (int64_t j = 0; j < nrhs; ++j) B[r * nrhs + j] -= f * B[c * nrhs + j];
+    }
+  }
+  return 0;
+}
+
+/*
+ * Cayley SGD step, left form:  A = G R^T - R G^T (skew),
+ * (I + lr/2 A) R+ = (I - lr/2 A) R.   A_out (d*d) may be NULL.
+ */
+int kto_cayley_step(const double *R, const double *G, int64_t d, double lr,
+                    double *Rout, double *A_out) {
+  const size_t dd = (size_t)d * (size_t)d;
+  double *GRt = (double *)malloc(sizeof(double) * dd);
+  double *A = (double *)malloc(sizeof(double) * dd);
+  double *M = (double *)malloc(sizeof(double) * dd);
+  double *N = (double *)malloc(sizeof(double) * dd);
+  mat_abt(G, R, d, GRt);
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) A[i * d + j] = GRt[i * d + j] - GRt[j * d + i];
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) {
+      const double e = (i == j) ? 1.0 : 0.0;
+      M[i * d + j] = e + 0.5 * lr * A[i * d + j];
+      N[i * d + j] = e - 0.5 * lr * A[i * d + j];
+    }
+  mat_ab(N, R, d, Rout);
+  const int rc = lu_solve(M, Rout, d, d);
+  if (A_out) memcpy(A_out, A, sizeof(double) * dd);
+  free(GRt); free(A); free(M); free(N);
+  return rc;
+}
+
+/*
+ * The same retraction written on the right of R (equal to the left form when R
+ * is orthogonal):  W = R^T G - G^T R,  R+ = R (I + lr/2 W)^-1 (I - lr/2 W).
+ * Solved as (I + lr/2 W)^T Z^T = R^T after forming R (.) via Z = R (I + lr/2 W)^-1.
+ */
+int kto_cayley_step_right(const double *R, const double *G, int64_t d, double lr,
+                          double *Rout) {
+  const size_t dd = (size_t)d * (size_t)d;
+  double *RtG = (double *)malloc(sizeof(double) * dd);
+  double *Mt = (double *)malloc(sizeof(double) * dd);
+  double *N = (double *)malloc(sizeof(double) * dd);
+  double *Zt = (double *)malloc(sizeof(double) * dd);
+  double *Z = (double *)malloc(sizeof(double) * dd);
+  mat_atb(R, G, d, RtG);
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) {
+      const double w = RtG[i * d + j] - RtG[j * d + i];
+      const double e = (i == j) ? 1.0 : 0.0;
+      Mt[j * d + i] = e + 0.5 * lr * w; /* transposed */
+      N[i * d + j] = e - 0.5 * lr * w;
+      Zt[j * d + i] = R[i * d + j];     /* R^T */
+    }
+  /* Z M = R  <=>  M^T Z^T = R^T */
+  const int rc = lu_solve(Mt, Zt, d, d);
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) Z[i * d + j] = Zt[j * d + i];
+  mat_ab(Z, N, d, Rout);
+  free(RtG); free(Mt); free(N); free(Zt); free(Z);
+  return rc;
+}
+
+/*
+ * Per-token symmetric int4 fake quantisation of Y = X R.
+ * The rotation is fp64; the rounding-critical part is carried out in IEEE
+ * single precision, one operation at a time:
+ *   yf = (float)y;  amax = max_j |yf|;  s = (clip * amax) / 7.0f   (or scales_in)
+ *   r = 1.0f / s;   q = clamp(rint(yf * r), -7, 7)   (round half to even)
+ *   yhat = q * s;   err = { sum_j (y - yhat)^2, sum_j y^2 }  in fp64 on y.
+ * A row with s == 0 gets codes 0 and yhat 0.
+ * scales_in, scales_out, codes, err may each be NULL.
+ */
+void kto_fakequant_int4(const double *X, const double *R, int64_t n, int64_t d,
+                        float clip, const float *scales_in, float *scales_out,
+                        int8_t *codes, double *err) {
+  double *Y = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
+  kto_rotate(X, R, n, d, Y);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) {
+    const double *y = Y + i * d;
+    float s;
+    if (scales_in) {
+      s = scales_in[i];
+    } else {
+      float amax = 0.0f;
+      for (int64_t j = 0; j < d; ++j) {
+        const float a = fabsf((float)y[j]);
+        if (a > amax) amax = a;
+      }
+      volatile float num = clip * amax;
+      s = num / 7.0f;
+    }
+    if (scales_out) scales_out[i] = s;
+    double e2 = 0.0, y2 = 0.0;
+    if (s > 0.0f) {
+      volatile float r = 1.0f / s;
+      for (int64_t j = 0; j < d; ++j) {
+        const float yf = (float)y[j];
+        volatile float t = yf * r;
+        float q = rintf(t);
+        if (q > 7.0f) q = 7.0f;
+        if (q < -7.0f) q = -7.0f;
+        if (codes) codes[i * d + j] = (int8_t)q;
+        const double yhat = (double)q * (double)s;
+        const double diff = y[j] - yhat;
+        e2 += diff * diff;
+        y2 += y[j] * y[j];
+      }
+    } else {
+      for (int64_t j = 0; j < d; ++j) {
+        if (codes) codes[i * d + j] = 0;
+        e2 += y[j] * y[j];
+        y2 += y[j] * y[j];
+      }
+    }
+    if (err) { err[2 * i] = e2; err[2 * i + 1] = y2; }
+  }
+  free(Y);
+}
