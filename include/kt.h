@@ -1,0 +1,149 @@
+/*
+ * kt.h -- C ABI of the MI355X (gfx950) KurTail rotation-learning library.
+ *
+ * The library covers the data-parallel hot path of KurTail (arXiv 2503.01483,
+ * "Learning the Rotations" / "Optimization in the Orthogonal Space"): rotate the
+ * stored block-input activations X by an orthogonal R, reduce every token row of
+ * Y = X R to its kurtosis (Background, "Kurtosis", Eq. 3), average into the loss,
+ * back-propagate to dL/dR = X^T (dL/dY), and retract R onto the orthogonal group
+ * with a Cayley step; plus the per-token symmetric int4 fake quantiser used to
+ * check the rotated activations (Background, "Uniform Quantization for k-bit
+ * Precision"; Setup).
+ *
+ * Conventions common to every entry point
+ *  - All data pointers are DEVICE pointers on the current HIP device unless the
+ *    comment says "host".  The caller owns every buffer; the library allocates,
+ *    frees and retains nothing, and keeps no state between calls.
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *    default stream).  No call synchronises with the host; scalar results stay
+ *    on the device.
+ *  - Argument errors are reported synchronously (nothing is enqueued, nothing is
+ *    written) through the return value; kt_last_error() gives the text.
+ *    Faults on the device surface at the caller's next synchronisation.
+ *  - Inputs and outputs must not overlap, except R in kt_cayley_step.
+ *  - `batch` independent problems are laid out back to back: problem b of X
+ *    starts at X + b*n*ldx elements, of R at R + b*d*ldr, of dR at dR + b*d*d.
+ *  - Results are deterministic: the same inputs give bitwise the same outputs
+ *    (fixed-order reductions, no floating-point atomics).
+ *  - `workspace` is device scratch of at least kt_workspace_bytes(...) bytes,
+ *    256-byte aligned; its contents are undefined before and after a call.
+ */
+#ifndef KT_H_
+#define KT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t kt_status;
+enum {
+  KT_OK = 0,
+  KT_ERR_INVALID_ARG = 1,         /* null pointer, non-positive size, bad scalar   */
+  KT_ERR_BAD_SHAPE = 2,           /* d not a multiple of 128, ld too small/unaligned */
+  KT_ERR_BAD_DTYPE = 3,           /* unsupported dtype combination                  */
+  KT_ERR_WORKSPACE_TOO_SMALL = 4,
+  KT_ERR_DEVICE = 5,              /* the HIP runtime refused a launch               */
+  KT_ERR_NOT_SUPPORTED = 6
+};
+
+typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
+typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2 } kt_op;
+
+/* Library version (major*10000 + minor*100 + patch). Host call. */
+int32_t kt_version(void);
+
+/* Text of the last error raised on the calling host thread ("" if none).
+ * Points to thread-local static storage; never free it. */
+const char* kt_last_error(void);
+
+/* Scratch bytes the given operation needs for these sizes (0 on bad sizes).
+ * For KT_OP_CAYLEY `n` is ignored.  Host call, launches nothing. */
+size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype);
+
+/*
+ * Kurtosis loss and its Euclidean gradient with respect to R.
+ *
+ *   Y = X R                                   ("Learning the Rotations": linear layer)
+ *   per token row i:  mu_i = mean_j y_ij, c = y - mu, m_k = mean_j c^k,
+ *                     kappa_i = m4 / m2^2     (Eq. 3; population moments, not excess)
+ *   loss = (1/n) sum_i f(kappa_i),  f(k) = k            if kappa_target == 0
+ *                                   f(k) = |k - target| otherwise   (kurtosis loss,
+ *                                   per-token-row reading; target 9/5 = uniform)
+ *   dL/dy_ij = s_i 4/(n d m2_i^2) [c_ij^3 - m3_i - kappa_i m2_i c_ij],  s_i = f'(kappa_i)
+ *   dR = X^T (dL/dY)
+ *
+ * Y and dL/dY as such never reach HBM in row-major form: Y is consumed in the GEMM
+ * epilogue (row moments), recomputed for the backward pass, and dL/dY is kept only
+ * as the token-minor scratch operand of the last GEMM.
+ *
+ *  X        [batch][n][ldx] row-major, x_dtype (KT_BF16, or KT_F32 for the fp32 path);
+ *           ldx >= d, rows 16-byte aligned (ldx % 8 == 0 for bf16, % 4 for fp32).
+ *  R        [batch][d][ldr] row-major, r_dtype.  With bf16 X, R may be the fp32 master
+ *           (rounded to bf16, nearest-even, inside) or already bf16; the loss and
+ *           gradient are those at the bf16-rounded R.  With fp32 X, R must be fp32.
+ *  d        multiple of 128.   n >= 1, any value (tail rows are masked).
+ *  loss     [batch] fp32, written.
+ *  row_kurt [batch][n] fp32 or NULL.
+ *  dR       [batch][d][d] fp32 or NULL (NULL: loss only, the backward GEMMs are skipped).
+ *  A row without spread (m2 <= 1e-5 of its mean square, fp32 resolution) counts with
+ *  kappa = 0 and contributes no gradient.
+ */
+kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                int64_t batch, int64_t n, int64_t d,
+                                kt_dtype x_dtype, kt_dtype r_dtype, float kappa_target,
+                                float* loss, float* row_kurt, float* dR,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One Cayley SGD step on the orthogonal group ("Optimization in the Orthogonal
+ * Space"; the paper names the optimiser and defers the formula to its reference):
+ *
+ *   A  = dR R^T - R dR^T          (skew-symmetric)
+ *   R+ = (I + lr/2 A)^-1 (I - lr/2 A) R
+ *
+ * The solve is the fixed-point iteration Z <- R - (lr/2) A (R + Z), run on the
+ * device until successive iterates agree to fp32 resolution; it converges when
+ * (lr/2)||A||_2 < 1.  No learning-rate clamp is applied: the caller chooses lr.
+ *
+ *  R        [batch][d][d] fp32, in/out (master copy).  d multiple of 128.
+ *  dR       [batch][d][d] fp32.
+ *  R_lowp   [batch][d][d] bf16 copy of the new R (nearest-even), or NULL.
+ *  ortho_err[batch] fp32: max_ij |(R+^T R+ - I)_ij| of the result, or NULL (skips one GEMM).
+ *  info     [batch] int32: number of iterations used, or -1 if the iteration did not
+ *           converge within the library's limit (R is then still written), or NULL.
+ */
+kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d,
+                         float lr, float* ortho_err, int32_t* info,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Rotate and fake-quantise to symmetric int4, one scale per token row
+ * (Background, "Uniform Quantization for k-bit Precision" with k = 4, b = 0;
+ * Setup: per-token dynamic symmetric quantisation; error as in Eq. 1):
+ *
+ *   y = x R (fp32 accumulation);  s_i = (clip_ratio * max_j |y_ij|) / 7   (or scales_in)
+ *   q_ij = clamp(rint(y_ij * (1/s_i)), -7, 7)   (fp32, round half to even)
+ *   err_i = { sum_j (y_ij - q_ij s_i)^2, sum_j y_ij^2 }
+ *
+ *  X, R, batch, n, d, dtypes: as for kt_kurtosis_loss_grad.
+ *  clip_ratio in (0, 1]; 1 is the plain symmetric scale.
+ *  scales_in  [batch][n] fp32 or NULL; if given it is used verbatim.
+ *  scales_out [batch][n] fp32 or NULL.
+ *  codes      [batch][n][d] int8, one code per byte in [-7, 7], or NULL.
+ *  err        [batch][n][2] fp32 or NULL.
+ *  A row with scale 0 gets codes 0.
+ */
+kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                   int64_t batch, int64_t n, int64_t d,
+                                   kt_dtype x_dtype, kt_dtype r_dtype, float clip_ratio,
+                                   const float* scales_in, float* scales_out, int8_t* codes,
+                                   float* err, void* workspace, size_t workspace_bytes,
+                                   void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KT_H_ */

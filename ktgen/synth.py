@@ -85,7 +85,7 @@ def random_orthogonal(d, seed=0, device="cpu"):
     a = torch.randn((d, d), generator=g, dtype=torch.float64)
     q, r = torch.linalg.qr(a)
     q = q * torch.sign(torch.diagonal(r)).unsqueeze(0)
-    return q.to(torch.float32).to(device)
+    return q.to(torch.float32).contiguous().to(device)
 
 
 def make_problem(name, *, seed=0, device="cpu", n=None, batch=None):

@@ -1,0 +1,24 @@
+"""MI355X-native KurTail rotation-learning step: thin Python binding.
+
+Argument marshalling only.  Every step of the path runs in the HIP kernels of
+``libkurtail.so`` (see ``include/kt.h`` for the C ABI); PyTorch is used for device
+memory and the current stream.  There is no CPU or eager fallback: if the library
+has not been built, importing the binding functions raises.
+"""
+from .binding import (  # noqa: F401
+    KT_F32,
+    KT_BF16,
+    KT_OP_LOSS_GRAD,
+    KT_OP_CAYLEY,
+    KT_OP_FAKEQUANT,
+    KtError,
+    lib,
+    lib_path,
+    kt_version,
+    kt_last_error,
+    kt_workspace_bytes,
+    kt_kurtosis_loss_grad,
+    kt_cayley_step,
+    kt_rotate_fakequant_int4,
+    Workspace,
+)

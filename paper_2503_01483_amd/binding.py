@@ -1,0 +1,155 @@
+"""ctypes binding of libkurtail.so; same names as the C entry points."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkurtail.so")
+_lib = None
+
+KT_F32, KT_BF16 = 0, 1
+KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT = 0, 1, 2
+
+EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
+           "kt_cayley_step", "kt_rotate_fakequant_int4")
+
+
+class KtError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"kt status {status}: {text}")
+        self.status = status
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Load the library; built on first use only if no built library is present."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build_library
+        build_library()
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    i32 = ctypes.c_int32
+    L.kt_version.restype = i32
+    L.kt_version.argtypes = []
+    L.kt_last_error.restype = ctypes.c_char_p
+    L.kt_last_error.argtypes = []
+    L.kt_workspace_bytes.restype = sz
+    L.kt_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+    L.kt_kurtosis_loss_grad.restype = i32
+    L.kt_kurtosis_loss_grad.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32,
+                                        vp, vp, vp, vp, sz, vp]
+    L.kt_cayley_step.restype = i32
+    L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
+    L.kt_rotate_fakequant_int4.restype = i32
+    L.kt_rotate_fakequant_int4.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32,
+                                           vp, vp, vp, vp, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def kt_version():
+    return int(lib().kt_version())
+
+
+def kt_last_error():
+    return lib().kt_last_error().decode()
+
+
+def kt_workspace_bytes(op, batch, n, d, x_dtype):
+    return int(lib().kt_workspace_bytes(op, batch, n, d, x_dtype))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return KT_BF16
+    if t.dtype == torch.float32:
+        return KT_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream) if hasattr(stream, "cuda_stream") else ctypes.c_void_p(stream)
+
+
+def _check(status):
+    if status != 0:
+        raise KtError(status, kt_last_error())
+
+
+class Workspace:
+    """A caller-owned scratch buffer (torch uint8 tensor) that grows on demand."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.buf = None
+
+    def get(self, nbytes):
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = None
+            self.buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=self.device)
+        return self.buf
+
+
+def _xr_dims(X, R):
+    if X.dim() == 2:
+        X = X.unsqueeze(0)
+    if R.dim() == 2:
+        R = R.unsqueeze(0)
+    batch, n, d = X.shape
+    assert R.shape == (batch, d, d), (X.shape, R.shape)
+    assert X.stride(2) == 1 and R.stride(2) == 1
+    assert batch == 1 or (X.stride(0) == n * X.stride(1) and R.stride(0) == d * R.stride(1))
+    return X, R, batch, n, d
+
+
+def kt_kurtosis_loss_grad(X, R, *, kappa_target=0.0, loss=None, row_kurt=None, dR=None,
+                          workspace=None, stream=None):
+    """loss [batch] fp32 (returned), optional row_kurt [batch][n] and dR [batch][d][d] outputs."""
+    X, R, batch, n, d = _xr_dims(X, R)
+    if loss is None:
+        loss = torch.empty(batch, dtype=torch.float32, device=X.device)
+    xdt = _dtype_code(X)
+    need = kt_workspace_bytes(KT_OP_LOSS_GRAD, batch, n, d, xdt)
+    ws = (workspace or Workspace(X.device)).get(need)
+    _check(lib().kt_kurtosis_loss_grad(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
+                                       _dtype_code(R), float(kappa_target), _ptr(loss),
+                                       _ptr(row_kurt), _ptr(dR), _ptr(ws), ws.numel(), _stream(stream)))
+    return loss
+
+
+def kt_cayley_step(R, dR, lr, *, R_lowp=None, ortho_err=None, info=None, workspace=None, stream=None):
+    """In-place Cayley step on R [batch][d][d] fp32."""
+    Rv = R if R.dim() == 3 else R.unsqueeze(0)
+    batch, d, _ = Rv.shape
+    assert Rv.is_contiguous() and dR.is_contiguous() and dR.numel() == Rv.numel()
+    assert R.dtype == torch.float32 and dR.dtype == torch.float32
+    need = kt_workspace_bytes(KT_OP_CAYLEY, batch, 0, d, KT_F32)
+    ws = (workspace or Workspace(R.device)).get(need)
+    _check(lib().kt_cayley_step(_ptr(Rv), _ptr(dR), _ptr(R_lowp), batch, d, float(lr), _ptr(ortho_err),
+                                _ptr(info), _ptr(ws), ws.numel(), _stream(stream)))
+    return R
+
+
+def kt_rotate_fakequant_int4(X, R, *, clip_ratio=1.0, scales_in=None, scales_out=None, codes=None,
+                             err=None, workspace=None, stream=None):
+    X, R, batch, n, d = _xr_dims(X, R)
+    xdt = _dtype_code(X)
+    need = kt_workspace_bytes(KT_OP_FAKEQUANT, batch, n, d, xdt)
+    ws = (workspace or Workspace(X.device)).get(need)
+    _check(lib().kt_rotate_fakequant_int4(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
+                                          _dtype_code(R), float(clip_ratio), _ptr(scales_in),
+                                          _ptr(scales_out), _ptr(codes), _ptr(err), _ptr(ws),
+                                          ws.numel(), _stream(stream)))

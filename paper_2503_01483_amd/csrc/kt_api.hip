@@ -1,0 +1,481 @@
+// kt_api.hip -- host side of libkurtail: argument checks, workspace layout, launch
+// sequences, and the extern "C" boundary declared in include/kt.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/kt.h"
+#include "kt_aux.h"
+
+namespace kt {
+
+// ------------------------------------------------------------------ errors --------
+static thread_local char g_err[512] = "";
+
+static kt_status fail(kt_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+// ------------------------------------------------------------------ tiles ---------
+using bf16 = __bf16;
+using TB_BIG = Tile<bf16, 256, 256, 2, 2>;   // d % 256 == 0
+using TB_M128 = Tile<bf16, 128, 256, 1, 4>;  // features on m, d % 256 != 0
+using TB_N128 = Tile<bf16, 256, 128, 4, 1>;  // features on n, d % 256 != 0
+using TB_128 = Tile<bf16, 128, 128, 2, 2>;   // d x d outputs, d % 256 != 0
+using TF = Tile<float, 128, 128, 2, 2>;      // fp32 path, every contraction
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+constexpr int kNumCUs = 256;
+constexpr int kCayleyMaxIters = 48;
+constexpr float kCayleyTol = 3e-7f;
+
+template <class TL, class Epi>
+static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const void* B, int64_t ldb,
+                        int64_t bsb, int N, int64_t K, int slabs_per_split, int batch,
+                        const Epi& epi, hipStream_t stream) {
+  static bool attr_done = false;
+  auto kern = gemm_nt_kernel<TL, Epi>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES) != hipSuccess)
+      return false;
+    attr_done = true;
+  }
+  GemmShape g;
+  g.A = A; g.B = B; g.lda = lda; g.ldb = ldb;
+  g.batch_stride_a = bsa; g.batch_stride_b = bsb;
+  g.M = M; g.N = N;
+  g.tiles_m = (int)ceil_div(M, TL::BM);
+  g.tiles_n = (int)ceil_div(N, TL::BN);
+  g.slabs_total = (int)(K / TL::BK);
+  g.slabs_per_split = slabs_per_split > 0 ? slabs_per_split : g.slabs_total;
+  g.split_k = (int)ceil_div(g.slabs_total, g.slabs_per_split);  // every split non-empty
+  g.tiles_total = g.tiles_m * g.tiles_n * g.split_k;
+  g.grid_padded = (int)round_up(g.tiles_total, 8);
+  hipLaunchKernelGGL(kern, dim3(g.grid_padded, batch), dim3(TL::NT), TL::LDS_BYTES, stream, g, epi);
+  return launch_ok();
+}
+
+// K slabs per split so that `tiles` output tiles give about one workgroup per CU,
+// with at least 8 slabs of work in each split.
+static int choose_slabs_per_split(int64_t tiles, int64_t slabs_total) {
+  int64_t s = ceil_div(kNumCUs, tiles);
+  const int64_t cap = slabs_total / 8 > 0 ? slabs_total / 8 : 1;
+  if (s > cap) s = cap;
+  if (s < 1) s = 1;
+  return (int)ceil_div(slabs_total, s);
+}
+
+// ------------------------------------------------------------------ workspace -----
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t o = off;
+    off = (size_t)round_up((int64_t)(off + bytes), 256);
+    return o;
+  }
+};
+
+struct LossGradPlan {
+  bool fp32;
+  size_t esz;
+  int64_t ldt;     // padded token count of the token-minor copies
+  int P;           // moment partials per token
+  int tiles_dd;    // tiles of the d x d output GEMM
+  int slabs_per_split, split_k;
+  size_t o_rt, o_part, o_coef, o_losspart, o_xt, o_gt, o_splitk, total;
+  int loss_blocks;
+};
+
+static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
+  LossGradPlan p;
+  p.fp32 = (xdt == KT_F32);
+  p.esz = p.fp32 ? 4 : 2;
+  p.ldt = round_up(n, 64);
+  int64_t slabs;
+  if (p.fp32) {
+    p.P = (int)ceil_div(d, TF::BM) * TF::WGM;
+    p.tiles_dd = (int)(ceil_div(d, TF::BM) * ceil_div(d, TF::BN));
+    slabs = p.ldt / TF::BK;
+  } else if (d % 256 == 0) {
+    p.P = (int)(d / TB_BIG::BM) * TB_BIG::WGM;
+    p.tiles_dd = (int)((d / 256) * (d / 256));
+    slabs = p.ldt / TB_BIG::BK;
+  } else {
+    p.P = (int)ceil_div(d, TB_M128::BM) * TB_M128::WGM;
+    p.tiles_dd = (int)(ceil_div(d, 128) * ceil_div(d, 128));
+    slabs = p.ldt / TB_128::BK;
+  }
+  p.slabs_per_split = choose_slabs_per_split((int64_t)p.tiles_dd * batch, slabs);
+  p.split_k = (int)ceil_div(slabs, p.slabs_per_split);
+  p.loss_blocks = (int)ceil_div(n, 256);
+  Carver c;
+  p.o_rt = c.take((size_t)batch * d * d * p.esz);
+  p.o_part = c.take((size_t)batch * p.P * n * 16);
+  p.o_coef = c.take((size_t)batch * n * 16);
+  p.o_losspart = c.take((size_t)batch * p.loss_blocks * 8);
+  p.o_xt = c.take((size_t)batch * d * p.ldt * p.esz);
+  p.o_gt = c.take((size_t)batch * d * p.ldt * p.esz);
+  p.o_splitk = c.take(p.split_k > 1 ? (size_t)p.split_k * batch * d * d * 4 : 0);
+  p.total = c.off;
+  return p;
+}
+
+struct CayleyPlan {
+  size_t o_m, o_b, o_rt, o_zt, o_u0, o_u1, o_delta, total;
+};
+
+static CayleyPlan plan_cayley(int64_t batch, int64_t d) {
+  CayleyPlan p;
+  Carver c;
+  const size_t mat = (size_t)batch * d * d * 4;
+  p.o_m = c.take(mat);  // M = dR R^T, later reused as the second U buffer
+  p.o_b = c.take(mat);
+  p.o_rt = c.take(mat);
+  p.o_zt = c.take(mat);
+  p.o_u0 = c.take(mat);
+  p.o_u1 = p.o_m;
+  p.o_delta = c.take((size_t)batch * kCayleyMaxIters * 4);
+  p.total = c.off;
+  return p;
+}
+
+struct QuantPlan {
+  bool fp32;
+  size_t esz;
+  int P, PN;
+  size_t o_rt, o_amax, o_scales, o_errpart, total;
+};
+
+static QuantPlan plan_quant(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
+  QuantPlan p;
+  p.fp32 = (xdt == KT_F32);
+  p.esz = p.fp32 ? 4 : 2;
+  if (p.fp32) {
+    p.P = (int)ceil_div(d, TF::BM) * TF::WGM;
+    p.PN = (int)ceil_div(d, TF::BN) * TF::WGN;
+  } else if (d % 256 == 0) {
+    p.P = (int)(d / 256) * TB_BIG::WGM;
+    p.PN = (int)(d / 256) * TB_BIG::WGN;
+  } else {
+    p.P = (int)ceil_div(d, TB_M128::BM) * TB_M128::WGM;
+    p.PN = (int)ceil_div(d, TB_N128::BN) * TB_N128::WGN;
+  }
+  Carver c;
+  p.o_rt = c.take((size_t)batch * d * d * p.esz);
+  p.o_amax = c.take((size_t)batch * p.P * n * 4);
+  p.o_scales = c.take((size_t)batch * n * 4);
+  p.o_errpart = c.take((size_t)batch * p.PN * n * 8);
+  p.total = c.off;
+  return p;
+}
+
+// ------------------------------------------------------------------ checks --------
+static kt_status check_xr(const void* X, int64_t ldx, const void* R, int64_t ldr, int64_t batch,
+                          int64_t n, int64_t d, kt_dtype xdt, kt_dtype rdt) {
+  if (!X || !R) return fail(KT_ERR_INVALID_ARG, "X and R must not be null");
+  if (batch < 1 || n < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch, n, d must be positive");
+  if (xdt != KT_F32 && xdt != KT_BF16) return fail(KT_ERR_BAD_DTYPE, "x_dtype must be KT_F32 or KT_BF16");
+  if (rdt != KT_F32 && rdt != KT_BF16) return fail(KT_ERR_BAD_DTYPE, "r_dtype must be KT_F32 or KT_BF16");
+  if (xdt == KT_F32 && rdt != KT_F32)
+    return fail(KT_ERR_BAD_DTYPE, "the fp32 path needs an fp32 R");
+  if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
+  if (d > 32768 || n > (int64_t)1 << 30 || batch > 65535)
+    return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 32768, n <= 2^30, batch <= 65535)");
+  const int64_t align = xdt == KT_F32 ? 4 : 8;
+  if (ldx < d || ldx % align != 0)
+    return fail(KT_ERR_BAD_SHAPE, "ldx = %lld must be >= d and a multiple of %lld", (long long)ldx,
+                (long long)align);
+  if (ldr < d) return fail(KT_ERR_BAD_SHAPE, "ldr = %lld must be >= d", (long long)ldr);
+  if ((reinterpret_cast<uintptr_t>(X) & 15) != 0)
+    return fail(KT_ERR_BAD_SHAPE, "X must be 16-byte aligned");
+  return KT_OK;
+}
+
+static kt_status check_ws(void* ws, size_t have, size_t need) {
+  if (!ws) return fail(KT_ERR_INVALID_ARG, "workspace must not be null");
+  if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0)
+    return fail(KT_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  if (have < need)
+    return fail(KT_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", have, need);
+  return KT_OK;
+}
+
+// R (fp32 or bf16, row-major) -> R^T in the GEMM dtype.
+template <typename Tout>
+static bool prep_rt(const void* R, int64_t ldr, kt_dtype rdt, Tout* RT, int64_t batch, int64_t d,
+                    hipStream_t st) {
+  dim3 grid((unsigned)ceil_div(d, 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
+  if (rdt == KT_F32)
+    hipLaunchKernelGGL((transpose_kernel<float, Tout>), grid, dim3(256), 0, st,
+                       static_cast<const float*>(R), ldr, d * ldr, RT, d, d * d, (int)d, (int)d, (int)d);
+  else
+    hipLaunchKernelGGL((transpose_kernel<bf16, Tout>), grid, dim3(256), 0, st,
+                       static_cast<const bf16*>(R), ldr, d * ldr, RT, d, d * d, (int)d, (int)d, (int)d);
+  return launch_ok();
+}
+
+// ------------------------------------------------------------------ loss + grad ---
+template <typename T, class TFWD, class TDD>
+static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx, const void* R,
+                               int64_t ldr, kt_dtype rdt, int64_t batch, int64_t n, int64_t d,
+                               float kappa_target, float* loss, float* row_kurt, float* dR,
+                               char* ws, hipStream_t st) {
+  T* RT = reinterpret_cast<T*>(ws + p.o_rt);
+  floatx4* part = reinterpret_cast<floatx4*>(ws + p.o_part);
+  floatx4* coef = reinterpret_cast<floatx4*>(ws + p.o_coef);
+  double* loss_part = reinterpret_cast<double*>(ws + p.o_losspart);
+  T* XT = reinterpret_cast<T*>(ws + p.o_xt);
+  T* GT = reinterpret_cast<T*>(ws + p.o_gt);
+  float* splitk = reinterpret_cast<float*>(ws + p.o_splitk);
+  const T* Xp = static_cast<const T*>(X);
+
+  // a0: R -> R^T in the GEMM dtype
+  if (!prep_rt<T>(R, ldr, rdt, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
+
+  // a1: forward GEMM (features on m, tokens on n) with the moment epilogue
+  {
+    EpiMoments<TFWD> e;
+    e.part = part; e.n_tokens = (int)n; e.d = (int)d; e.P = p.P;
+    if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "forward GEMM launch failed");
+  }
+  // a2: per-token finalisation and loss
+  hipLaunchKernelGGL(finalize_rows_kernel, dim3(p.loss_blocks, (unsigned)batch), dim3(256), 0, st, part,
+                     p.P, (int)n, (int)d, kappa_target, coef, row_kurt, loss_part);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "finalize_rows launch failed");
+  hipLaunchKernelGGL(finalize_loss_kernel, dim3((unsigned)batch), dim3(256), 0, st, loss_part,
+                     p.loss_blocks, (int)n, loss);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "finalize_loss launch failed");
+  if (!dR) return KT_OK;
+
+  // token-minor copy of X for the last GEMM (zero padded to ldt tokens)
+  {
+    dim3 grid((unsigned)(p.ldt / 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
+    hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.ldt,
+                       d * p.ldt, (int)n, (int)p.ldt, (int)d);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "X transpose launch failed");
+  }
+  // a3: recompute Y, write dL/dY token-minor
+  {
+    EpiGrad<TFWD> e;
+    e.coef = coef; e.GT = GT; e.ldt = p.ldt; e.n_tokens = (int)n; e.d = (int)d;
+    if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "backward recompute GEMM launch failed");
+  }
+  // a4: dR = X^T G, split over tokens
+  {
+    EpiStore<TDD> e;
+    e.ldc = d; e.M = (int)d; e.N = (int)d;
+    if (p.split_k > 1) {
+      e.C = splitk; e.batch_stride = d * d; e.split_stride = batch * d * d;
+    } else {
+      e.C = dR; e.batch_stride = d * d; e.split_stride = 0;
+    }
+    if (!launch_gemm<TDD>(XT, p.ldt, d * p.ldt, (int)d, GT, p.ldt, d * p.ldt, (int)d, p.ldt,
+                          p.slabs_per_split, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "gradient GEMM launch failed");
+    if (p.split_k > 1) {
+      const int64_t count = batch * d * d;
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(ceil_div(count, 256) < 4096 ? ceil_div(count, 256) : 4096)),
+                         dim3(256), 0, st, splitk, count, p.split_k, dR, count);
+      if (!launch_ok()) return fail(KT_ERR_DEVICE, "split-K reduce launch failed");
+    }
+  }
+  return KT_OK;
+}
+
+// ------------------------------------------------------------------ fake-quant ----
+template <typename T, class TFWD, class TQ>
+static kt_status run_quant(const QuantPlan& p, const void* X, int64_t ldx, const void* R, int64_t ldr,
+                           kt_dtype rdt, int64_t batch, int64_t n, int64_t d, float clip,
+                           const float* scales_in, float* scales_out, int8_t* codes, float* err,
+                           char* ws, hipStream_t st) {
+  T* RT = reinterpret_cast<T*>(ws + p.o_rt);
+  float* amax = reinterpret_cast<float*>(ws + p.o_amax);
+  float* scales_ws = reinterpret_cast<float*>(ws + p.o_scales);
+  float2* errpart = reinterpret_cast<float2*>(ws + p.o_errpart);
+  const T* Xp = static_cast<const T*>(X);
+  if (!prep_rt<T>(R, ldr, rdt, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
+  const float* scales = scales_in;
+  if (!scales_in) {
+    EpiAmax<TFWD> e;
+    e.part = amax; e.n_tokens = (int)n; e.d = (int)d; e.P = p.P;
+    if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "amax GEMM launch failed");
+    hipLaunchKernelGGL(quant_scale_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)batch), dim3(256),
+                       0, st, amax, p.P, n, clip, scales_ws, scales_out);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "scale kernel launch failed");
+    scales = scales_ws;
+  } else if (scales_out) {
+    if (hipMemcpyAsync(scales_out, scales_in, (size_t)batch * n * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+      return fail(KT_ERR_DEVICE, "scale copy failed");
+  }
+  if (!codes && !err) return KT_OK;
+  {
+    EpiQuant<TQ> e;
+    e.scales = scales; e.codes = codes; e.err_part = err ? errpart : nullptr;
+    e.n_tokens = (int)n; e.d = (int)d; e.PN = p.PN;
+    if (!launch_gemm<TQ>(Xp, ldx, n * ldx, (int)n, RT, d, d * d, (int)d, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "quantise GEMM launch failed");
+  }
+  if (err) {
+    hipLaunchKernelGGL(quant_err_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)batch), dim3(256), 0,
+                       st, errpart, p.PN, n, reinterpret_cast<float2*>(err));
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "error reduce launch failed");
+  }
+  return KT_OK;
+}
+
+}  // namespace kt
+
+using namespace kt;
+
+// =================================================================== C ABI =========
+extern "C" {
+
+int32_t kt_version(void) { return 100; }
+
+const char* kt_last_error(void) { return g_err; }
+
+size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype) {
+  if (batch < 1 || d < 1 || d % 128 != 0) return 0;
+  if (x_dtype != KT_F32 && x_dtype != KT_BF16) return 0;
+  switch (op) {
+    case KT_OP_LOSS_GRAD:
+      if (n < 1) return 0;
+      return plan_loss_grad(batch, n, d, x_dtype).total;
+    case KT_OP_CAYLEY:
+      return plan_cayley(batch, d).total;
+    case KT_OP_FAKEQUANT:
+      if (n < 1) return 0;
+      return plan_quant(batch, n, d, x_dtype).total;
+    default:
+      return 0;
+  }
+}
+
+kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype,
+                                kt_dtype r_dtype, float kappa_target, float* loss, float* row_kurt,
+                                float* dR, void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
+  if (s != KT_OK) return s;
+  if (!loss) return fail(KT_ERR_INVALID_ARG, "loss must not be null");
+  if (!(kappa_target >= 0.f)) return fail(KT_ERR_INVALID_ARG, "kappa_target must be >= 0");
+  const LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype);
+  s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p.fp32)
+    return run_loss_grad<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss,
+                                        row_kurt, dR, ws, st);
+  if (d % 256 == 0)
+    return run_loss_grad<bf16, TB_BIG, TB_BIG>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
+                                               loss, row_kurt, dR, ws, st);
+  return run_loss_grad<bf16, TB_M128, TB_128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
+                                              loss, row_kurt, dR, ws, st);
+}
+
+kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d, float lr,
+                         float* ortho_err, int32_t* info, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  g_err[0] = 0;
+  if (!R || !dR) return fail(KT_ERR_INVALID_ARG, "R and dR must not be null");
+  if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
+  if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
+  if (d > 32768 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range");
+  if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
+  const CayleyPlan p = plan_cayley(batch, d);
+  kt_status s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* Mm = reinterpret_cast<float*>(ws + p.o_m);
+  float* Bm = reinterpret_cast<float*>(ws + p.o_b);
+  float* Rt = reinterpret_cast<float*>(ws + p.o_rt);
+  float* Zt = reinterpret_cast<float*>(ws + p.o_zt);
+  float* U[2] = {reinterpret_cast<float*>(ws + p.o_u0), reinterpret_cast<float*>(ws + p.o_u1)};
+  unsigned* delta = reinterpret_cast<unsigned*>(ws + p.o_delta);
+  const int D = (int)d;
+  const int64_t dd = d * d;
+
+  // M = dR R^T
+  {
+    EpiStore<TF> e;
+    e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
+    if (!launch_gemm<TF>(dR, d, dd, D, R, d, dd, D, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "dR R^T GEMM launch failed");
+  }
+  // delta[it] collects max |Zt_new - Zt_old| of iteration it through atomicMax
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, delta, batch * kCayleyMaxIters, 0u);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "fill launch failed");
+  hipLaunchKernelGGL(cayley_setup_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Mm, R,
+                     D, 0.5f * lr, Bm, Rt, Zt, U[0]);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley set-up launch failed");
+  // fixed point in transposed space: Zt <- Rt - U Bm^T, U <- Rt + Zt
+  for (int it = 0; it < kCayleyMaxIters; ++it) {
+    EpiCayleyIter<TF> e;
+    e.Rt = Rt; e.Zt = Zt; e.Unew = U[(it + 1) & 1]; e.delta = delta;
+    e.d = D; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
+    if (!launch_gemm<TF>(U[it & 1], d, dd, D, Bm, d, dd, D, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
+  }
+  hipLaunchKernelGGL(cayley_finish_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Zt, D,
+                     R, static_cast<__bf16*>(R_lowp), delta, kCayleyMaxIters, kCayleyTol, info);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley wrap-up launch failed");
+  if (ortho_err) {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<unsigned*>(ortho_err),
+                       batch, 0u);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "fill launch failed");
+    EpiOrtho<TF> e;
+    e.err = reinterpret_cast<unsigned*>(ortho_err); e.d = D;
+    // Zt Zt^T = R^T R
+    if (!launch_gemm<TF>(Zt, d, dd, D, Zt, d, dd, D, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "orthogonality GEMM launch failed");
+    hipLaunchKernelGGL(ortho_diag_kernel, dim3(D, (unsigned)batch), dim3(256), 0, st, Zt, D,
+                       reinterpret_cast<unsigned*>(ortho_err));
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "orthogonality diagonal launch failed");
+  }
+  return KT_OK;
+}
+
+kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                   int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype,
+                                   kt_dtype r_dtype, float clip_ratio, const float* scales_in,
+                                   float* scales_out, int8_t* codes, float* err, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
+  if (s != KT_OK) return s;
+  if (!(clip_ratio > 0.f && clip_ratio <= 1.f))
+    return fail(KT_ERR_INVALID_ARG, "clip_ratio must be in (0, 1]");
+  if (!scales_out && !codes && !err) return fail(KT_ERR_INVALID_ARG, "no output requested");
+  const QuantPlan p = plan_quant(batch, n, d, x_dtype);
+  s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p.fp32)
+    return run_quant<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
+                                    scales_out, codes, err, ws, st);
+  if (d % 256 == 0)
+    return run_quant<bf16, TB_BIG, TB_BIG>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
+                                           scales_out, codes, err, ws, st);
+  return run_quant<bf16, TB_M128, TB_N128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
+                                           scales_out, codes, err, ws, st);
+}
+
+}  // extern "C"

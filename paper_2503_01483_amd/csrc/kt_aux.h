@@ -1,0 +1,254 @@
+// kt_aux.h -- the small bandwidth-bound kernels around the GEMMs: layout
+// preparation, per-token finalisation, fixed-order reductions.
+#pragma once
+#include "kt_epilogues.h"
+
+namespace kt {
+
+template <typename Tin>
+__device__ __forceinline__ float to_float(Tin v) { return (float)v; }
+
+// out[c*ldo + r] = in[r*ldi + c] for r < rows, c < cols; columns r in [rows, rows_pad)
+// of `out` are zero-filled.  64 x 64 tiles through LDS, 256 threads.
+// grid = (ceil(rows_pad/64), ceil(cols/64), batch)
+template <typename Tin, typename Tout>
+__global__ __launch_bounds__(256) void transpose_kernel(const Tin* __restrict__ in, int64_t ldi,
+                                                        int64_t in_batch_stride,
+                                                        Tout* __restrict__ out, int64_t ldo,
+                                                        int64_t out_batch_stride, int rows,
+                                                        int rows_pad, int cols) {
+  __shared__ float tile[64][65];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  in += (int64_t)blockIdx.z * in_batch_stride;
+  out += (int64_t)blockIdx.z * out_batch_stride;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int r = r0 + ty + 4 * i, c = c0 + tx;
+    float v = 0.f;
+    if (r < rows && c < cols) v = to_float(in[(int64_t)r * ldi + c]);
+    tile[ty + 4 * i][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int c = c0 + ty + 4 * i, r = r0 + tx;
+    if (c < cols && r < rows_pad) out[(int64_t)c * ldo + r] = from_float<Tout>(tile[tx][ty + 4 * i]);
+  }
+}
+
+// Row-major copy with dtype conversion: out[r*ldo + c] = in[r*ldi + c].
+template <typename Tin, typename Tout>
+__global__ __launch_bounds__(256) void convert_kernel(const Tin* __restrict__ in, int64_t ldi,
+                                                      int64_t in_batch_stride,
+                                                      Tout* __restrict__ out, int64_t ldo,
+                                                      int64_t out_batch_stride, int rows, int cols) {
+  in += (int64_t)blockIdx.z * in_batch_stride;
+  out += (int64_t)blockIdx.z * out_batch_stride;
+  const int64_t total = (int64_t)rows * cols;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int r = (int)(i / cols), c = (int)(i % cols);
+    out[(int64_t)r * ldo + c] = from_float<Tout>(to_float(in[(int64_t)r * ldi + c]));
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(unsigned* p, int64_t count, unsigned v) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+    p[i] = v;
+}
+
+__device__ __forceinline__ double block_sum_256(double v, double* sh) {
+  const int tid = threadIdx.x;
+  sh[tid] = v;
+  __syncthreads();
+#pragma unroll
+  for (int s = 128; s >= 1; s >>= 1) {
+    if (tid < s) sh[tid] += sh[tid + s];
+    __syncthreads();
+  }
+  return sh[0];
+}
+
+// Per token: add the P partial raw sums in fixed order (fp64), turn them into the
+// central moments of Eq. 3, kappa, the loss term and the coefficients the backward
+// epilogue needs.  One thread per token; grid = (ceil(n/256), batch).
+__global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __restrict__ part, int P,
+                                                            int n, int d, float kappa_target,
+                                                            floatx4* __restrict__ coef,
+                                                            float* __restrict__ row_kurt,
+                                                            double* __restrict__ loss_part) {
+  __shared__ double sh[256];
+  const int batch = blockIdx.y;
+  const int token = blockIdx.x * 256 + threadIdx.x;
+  double term = 0.0;
+  if (token < n) {
+    double S1 = 0, S2 = 0, S3 = 0, S4 = 0;
+    for (int p = 0; p < P; ++p) {
+      const floatx4 v = part[((int64_t)batch * P + p) * n + token];
+      S1 += v[0]; S2 += v[1]; S3 += v[2]; S4 += v[3];
+    }
+    const double inv_d = 1.0 / (double)d;
+    const double mu = S1 * inv_d, r2 = S2 * inv_d, r3 = S3 * inv_d, r4 = S4 * inv_d;
+    const double m2 = r2 - mu * mu;
+    const double m3 = r3 - 3.0 * mu * r2 + 2.0 * mu * mu * mu;
+    const double m4 = r4 - 4.0 * mu * r3 + 6.0 * mu * mu * r2 - 3.0 * mu * mu * mu * mu;
+    const bool ok = m2 > 1e-5 * r2;  // fp32 sums cannot resolve less spread than this
+    double kappa = 0.0, alpha = 0.0, beta = 0.0;
+    if (ok) {
+      kappa = m4 / (m2 * m2);
+      double sgn = 1.0;
+      if (kappa_target != 0.f) {
+        const double dk = kappa - (double)kappa_target;
+        sgn = (dk > 0.0) - (dk < 0.0);
+        term = fabs(dk);
+      } else {
+        term = kappa;
+      }
+      alpha = sgn * 4.0 / ((double)n * (double)d * m2 * m2);
+      beta = kappa * m2;
+    } else if (kappa_target != 0.f) {
+      term = fabs((double)kappa_target);
+    }
+    floatx4 c = {(float)alpha, (float)mu, (float)beta, (float)m3};
+    coef[(int64_t)batch * n + token] = c;
+    if (row_kurt) row_kurt[(int64_t)batch * n + token] = (float)kappa;
+  }
+  const double s = block_sum_256(term, sh);
+  if (threadIdx.x == 0) loss_part[(int64_t)batch * gridDim.x + blockIdx.x] = s;
+}
+
+// loss[batch] = (sum of the block partials, fixed order) / n.  grid = batch blocks.
+__global__ __launch_bounds__(256) void finalize_loss_kernel(const double* __restrict__ loss_part,
+                                                            int nblocks, int n,
+                                                            float* __restrict__ loss) {
+  __shared__ double sh[256];
+  const int batch = blockIdx.x;
+  double v = 0.0;
+  for (int i = threadIdx.x; i < nblocks; i += 256) v += loss_part[(int64_t)batch * nblocks + i];
+  const double s = block_sum_256(v, sh);
+  if (threadIdx.x == 0) loss[batch] = (float)(s / (double)n);
+}
+
+// out[i] = sum_s part[s*stride + i], s ascending.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
+                                                            int64_t stride, int splits,
+                                                            float* __restrict__ out, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+    float v = part[i];
+    for (int s = 1; s < splits; ++s) v += part[(int64_t)s * stride + i];
+    out[i] = v;
+  }
+}
+
+// Cayley set-up: from M = dR R^T build  Bm = (lr/2)(M - M^T)  (exactly skew),
+// Rt = R^T, Zt0 = Rt, U0 = 2 Rt.  32 x 32 tiles; grid = (d/32, d/32, batch).
+__global__ __launch_bounds__(256) void cayley_setup_kernel(const float* __restrict__ Mm,
+                                                           const float* __restrict__ R, int d,
+                                                           float half_lr, float* __restrict__ Bm,
+                                                           float* __restrict__ Rt,
+                                                           float* __restrict__ Zt,
+                                                           float* __restrict__ U0) {
+  __shared__ float tm[32][33];
+  __shared__ float tr[32][33];
+  const int64_t bo = (int64_t)blockIdx.z * d * d;
+  const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  // load the mirrored tile (rows j0.., cols i0..) of M and of R
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int rr = ty + 8 * k;
+    tm[rr][tx] = Mm[bo + (int64_t)(j0 + rr) * d + i0 + tx];
+    tr[rr][tx] = R[bo + (int64_t)(j0 + rr) * d + i0 + tx];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int rr = ty + 8 * k;  // row i0+rr, col j0+tx of the outputs
+    const int64_t idx = bo + (int64_t)(i0 + rr) * d + j0 + tx;
+    const float m_ij = Mm[idx];
+    const float m_ji = tm[tx][rr];
+    Bm[idx] = half_lr * (m_ij - m_ji);
+    const float rt = tr[tx][rr];  // R[j0+tx][i0+rr] = Rt[i0+rr][j0+tx]
+    Rt[idx] = rt;
+    Zt[idx] = rt;
+    U0[idx] = 2.f * rt;
+  }
+}
+
+// Cayley wrap-up: R = Zt^T (and its bf16 copy), info = iterations used or -1.
+__global__ __launch_bounds__(256) void cayley_finish_kernel(const float* __restrict__ Zt, int d,
+                                                            float* __restrict__ R,
+                                                            __bf16* __restrict__ R_lowp,
+                                                            const unsigned* __restrict__ delta,
+                                                            int max_iters, float tol,
+                                                            int32_t* __restrict__ info) {
+  __shared__ float tz[32][33];
+  const int64_t bo = (int64_t)blockIdx.z * d * d;
+  const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int rr = ty + 8 * k;
+    tz[rr][tx] = Zt[bo + (int64_t)(j0 + rr) * d + i0 + tx];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int rr = ty + 8 * k;
+    const int64_t idx = bo + (int64_t)(i0 + rr) * d + j0 + tx;
+    const float v = tz[tx][rr];
+    R[idx] = v;
+    if (R_lowp) R_lowp[idx] = (__bf16)v;
+  }
+  if (info && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    int used = -1;
+    for (int k = 0; k < max_iters; ++k) {
+      if (__uint_as_float(delta[(int64_t)blockIdx.z * max_iters + k]) <= tol) { used = k + 1; break; }
+    }
+    info[blockIdx.z] = used;
+  }
+}
+
+// Diagonal of Zt Zt^T - I: | sum_k Zt[m][k]^2 - 1 | summed in fp64, folded into err[batch]
+// (bit pattern of a non-negative float) by atomicMax.  grid = (d, batch).
+__global__ __launch_bounds__(256) void ortho_diag_kernel(const float* __restrict__ Zt, int d,
+                                                         unsigned* __restrict__ err) {
+  __shared__ double sh[256];
+  const float* row = Zt + ((int64_t)blockIdx.y * d + blockIdx.x) * d;
+  double s = 0.0;
+  for (int k = threadIdx.x; k < d; k += 256) s += (double)row[k] * (double)row[k];
+  s = block_sum_256(s, sh);
+  if (threadIdx.x == 0) atomicMax(&err[blockIdx.y], abs_bits((float)(s - 1.0)));
+}
+
+// Fake-quant scales: amax over the P partials, s = (clip * amax) / 7 in fp32.
+__global__ __launch_bounds__(256) void quant_scale_kernel(const float* __restrict__ part, int P,
+                                                          int64_t n_total_per_batch, float clip,
+                                                          float* __restrict__ scales_ws,
+                                                          float* __restrict__ scales_out) {
+  const int batch = blockIdx.y;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_total_per_batch) return;
+  float a = 0.f;
+  for (int p = 0; p < P; ++p) a = fmaxf(a, part[((int64_t)batch * P + p) * n_total_per_batch + t]);
+  const float s = __fdiv_rn(__fmul_rn(clip, a), 7.0f);
+  scales_ws[batch * n_total_per_batch + t] = s;
+  if (scales_out) scales_out[batch * n_total_per_batch + t] = s;
+}
+
+// err[token] = sum over the PN partial pairs, fixed order.
+__global__ __launch_bounds__(256) void quant_err_kernel(const float2* __restrict__ part, int PN,
+                                                        int64_t n, float2* __restrict__ err) {
+  const int batch = blockIdx.y;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n) return;
+  float e = 0.f, y = 0.f;
+  for (int p = 0; p < PN; ++p) {
+    const float2 v = part[((int64_t)batch * PN + p) * n + t];
+    e += v.x;
+    y += v.y;
+  }
+  err[batch * n + t] = make_float2(e, y);
+}
+
+}  // namespace kt

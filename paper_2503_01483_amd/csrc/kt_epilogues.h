@@ -1,0 +1,293 @@
+// kt_epilogues.h -- what each GEMM on the path does with its accumulator tile.
+//
+// Every functor is called as epi(acc, batch, tm, tn, ks, m0, n0) once the main
+// loop is done; `skip(batch)` lets a launch return early (used by the Cayley
+// fixed-point iteration once it has converged).
+#pragma once
+#include "kt_gemm.h"
+
+namespace kt {
+
+template <typename T>
+__device__ __forceinline__ T from_float(float v);
+template <>
+__device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ __bf16 from_float<__bf16>(float v) { return (__bf16)v; }
+
+struct EpiBase {
+  __device__ __forceinline__ bool skip(int) const { return false; }
+};
+
+// ---- forward pass: per-token raw moments of y over the hidden dimension ----------
+// m = output feature (reduced in registers), n = token (one per lane).
+// part[(batch*P + p)*n_tokens + token] = {sum y, sum y^2, sum y^3, sum y^4} over the
+// WTM features wave-row p = tm*WGM + wm owns.
+template <class TL>
+struct EpiMoments : EpiBase {
+  floatx4* part;
+  int n_tokens, d, P;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int tm,
+                                             int, int, int m0, int n0) const {
+    const Frag<TL> f;
+    const int p = tm * TL::WGM + f.wm;
+#pragma unroll
+    for (int nb = 0; nb < TL::NB; ++nb) {
+      float s1 = 0.f, s2 = 0.f, s3 = 0.f, s4 = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < TL::MB; ++mb) {
+        if (m0 + f.m_block(mb) < d) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float y = acc[mb][nb][r];
+            const float y2 = y * y;
+            s1 += y;
+            s2 += y2;
+            s3 = fmaf(y2, y, s3);
+            s4 = fmaf(y2, y2, s4);
+          }
+        }
+      }
+      s1 += __shfl_xor(s1, 32);
+      s2 += __shfl_xor(s2, 32);
+      s3 += __shfl_xor(s3, 32);
+      s4 += __shfl_xor(s4, 32);
+      const int token = n0 + f.n_of(nb);
+      if (f.half == 0 && token < n_tokens) {
+        floatx4 v = {s1, s2, s3, s4};
+        part[((int64_t)batch * P + p) * n_tokens + token] = v;
+      }
+    }
+  }
+};
+
+// ---- backward pass: recomputed y -> dL/dy, stored token-minor ---------------------
+// coef[token] = {alpha, mu, beta, m3};  g = alpha * (c (c^2 - beta) - m3), c = y - mu.
+// GT[(batch*d + feature)*ldt + token]; tokens in [n_tokens, ldt) are written as zero
+// so the padded K range of the following X^T G GEMM contributes nothing.
+template <class TL>
+struct EpiGrad : EpiBase {
+  using T = typename TL::T;
+  const floatx4* coef;
+  T* GT;
+  int64_t ldt;
+  int n_tokens, d;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
+                                             int, int, int m0, int n0) const {
+    const Frag<TL> f;
+#pragma unroll
+    for (int nb = 0; nb < TL::NB; ++nb) {
+      const int token = n0 + f.n_of(nb);
+      if (token >= ldt) continue;
+      const bool valid = token < n_tokens;
+      floatx4 c4 = {0.f, 0.f, 0.f, 0.f};
+      if (valid) c4 = coef[(int64_t)batch * n_tokens + token];
+      const float alpha = c4[0], mu = c4[1], beta = c4[2], m3 = c4[3];
+#pragma unroll
+      for (int mb = 0; mb < TL::MB; ++mb) {
+        if (m0 + f.m_block(mb) < d) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float c = acc[mb][nb][r] - mu;
+            float g = alpha * fmaf(c, fmaf(c, c, -beta), -m3);
+            if (!valid) g = 0.f;
+            const int feat = m0 + f.m_of(mb, r);
+            GT[((int64_t)batch * d + feat) * ldt + token] = from_float<T>(g);
+          }
+        }
+      }
+    }
+  }
+};
+
+// ---- plain fp32 store, optionally into split-K partial slabs ---------------------
+// C[ks*split_stride + batch*batch_stride + m*ldc + n]
+template <class TL>
+struct EpiStore : EpiBase {
+  float* C;
+  int64_t ldc, batch_stride, split_stride;
+  int M, N;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
+                                             int, int ks, int m0, int n0) const {
+    const Frag<TL> f;
+    float* base = C + (int64_t)ks * split_stride + (int64_t)batch * batch_stride;
+#pragma unroll
+    for (int mb = 0; mb < TL::MB; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < TL::NB; ++nb) {
+        const int n = n0 + f.n_of(nb);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + f.m_of(mb, r);
+          if (m < M && n < N) base[(int64_t)m * ldc + n] = acc[mb][nb][r];
+        }
+      }
+  }
+};
+
+// Max of |x| taken on bit patterns: for non-negative floats the unsigned order is the
+// numeric order, +inf sits above every finite value and NaN above +inf, so a NaN
+// anywhere survives the reduction instead of being dropped as fmaxf would.
+__device__ __forceinline__ unsigned abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+__device__ __forceinline__ unsigned umax(unsigned a, unsigned b) { return a > b ? a : b; }
+__device__ __forceinline__ unsigned wave_umax(unsigned v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = umax(v, (unsigned)__shfl_xor((int)v, o));
+  return v;
+}
+
+// ---- Cayley fixed point, in transposed space ---------------------------------------
+// acc = U_k * B^T.  Zt_new = Rt - acc;  U_{k+1} = Rt + Zt_new;
+// delta[it] = max |Zt_new - Zt_old| (bit pattern of a non-negative float, max is
+// order independent so the result is deterministic).  The launch for iteration `it`
+// returns at once when iteration it-1 already met the tolerance.
+template <class TL>
+struct EpiCayleyIter {
+  const float* Rt;
+  float* Zt;
+  float* Unew;
+  unsigned* delta;  // [batch][max_iters]
+  int d, it, max_iters;
+  float tol;
+  __device__ __forceinline__ bool skip(int batch) const {
+    if (it == 0) return false;
+    const unsigned bits = delta[(int64_t)batch * max_iters + it - 1];
+    if (!(__uint_as_float(bits) <= tol)) return false;
+    // converged earlier: hand the small delta on so that later launches return too
+    if (blockIdx.x == 0 && threadIdx.x == 0) delta[(int64_t)batch * max_iters + it] = bits;
+    return true;
+  }
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
+                                             int, int, int m0, int n0) const {
+    const Frag<TL> f;
+    const int64_t bo = (int64_t)batch * d * d;
+    unsigned dmax = 0u;
+#pragma unroll
+    for (int mb = 0; mb < TL::MB; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < TL::NB; ++nb) {
+        const int n = n0 + f.n_of(nb);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + f.m_of(mb, r);
+          if (m < d && n < d) {
+            const int64_t idx = bo + (int64_t)m * d + n;
+            const float rt = Rt[idx];
+            const float z = rt - acc[mb][nb][r];
+            dmax = umax(dmax, abs_bits(z - Zt[idx]));
+            Zt[idx] = z;
+            Unew[idx] = rt + z;
+          }
+        }
+      }
+    dmax = wave_umax(dmax);
+    if (f.lane == 0) atomicMax(&delta[(int64_t)batch * max_iters + it], dmax);
+  }
+};
+
+// ---- orthogonality check: max |acc_mn| over m != n -----------------------------------
+// The diagonal (sums of squares close to 1, where fp32 accumulation loses ~1e-7 per
+// entry) is left to ortho_diag_kernel, which sums in fp64.
+template <class TL>
+struct EpiOrtho : EpiBase {
+  unsigned* err;  // [batch], bit pattern of a non-negative float, zeroed before launch
+  int d;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
+                                             int, int, int m0, int n0) const {
+    const Frag<TL> f;
+    unsigned e = 0u;
+#pragma unroll
+    for (int mb = 0; mb < TL::MB; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < TL::NB; ++nb) {
+        const int n = n0 + f.n_of(nb);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + f.m_of(mb, r);
+          if (m < d && n < d && m != n) e = umax(e, abs_bits(acc[mb][nb][r]));
+        }
+      }
+    e = wave_umax(e);
+    if (f.lane == 0) atomicMax(&err[batch], e);
+  }
+};
+
+// ---- fake-quant pass A: per-token max |y| -----------------------------------------
+// same orientation as EpiMoments; part[(batch*P + p)*n_tokens + token]
+template <class TL>
+struct EpiAmax : EpiBase {
+  float* part;
+  int n_tokens, d, P;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int tm,
+                                             int, int, int m0, int n0) const {
+    const Frag<TL> f;
+    const int p = tm * TL::WGM + f.wm;
+#pragma unroll
+    for (int nb = 0; nb < TL::NB; ++nb) {
+      float a = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < TL::MB; ++mb)
+        if (m0 + f.m_block(mb) < d) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) a = fmaxf(a, fabsf(acc[mb][nb][r]));
+        }
+      a = fmaxf(a, __shfl_xor(a, 32));
+      const int token = n0 + f.n_of(nb);
+      if (f.half == 0 && token < n_tokens) part[((int64_t)batch * P + p) * n_tokens + token] = a;
+    }
+  }
+};
+
+// ---- fake-quant pass B: quantise the recomputed y ----------------------------------
+// Orientation swapped: m = token, n = feature, so a lane group writes 32 consecutive
+// code bytes of one token.  q = clamp(rint(y * (1/s)), -7, 7) in fp32; per-token error
+// sums are reduced over the 32 feature lanes and stored per wave-column
+// pe[(batch*PN + pn)*n_tokens + token] = {sum (y - q s)^2, sum y^2}.
+template <class TL>
+struct EpiQuant : EpiBase {
+  const float* scales;  // [batch][n_tokens]
+  int8_t* codes;        // [batch][n_tokens][d] or null
+  float2* err_part;     // or null
+  int n_tokens, d, PN;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
+                                             int tn, int, int m0, int n0) const {
+    const Frag<TL> f;
+    const int pn = tn * TL::WGN + f.wn;
+#pragma unroll
+    for (int mb = 0; mb < TL::MB; ++mb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int token = m0 + f.m_of(mb, r);
+        const bool tv = token < n_tokens;
+        const float s = tv ? scales[(int64_t)batch * n_tokens + token] : 0.f;
+        const float rinv = s > 0.f ? __fdiv_rn(1.0f, s) : 0.f;
+        float e2 = 0.f, y2 = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < TL::NB; ++nb) {
+          const int feat = n0 + f.n_of(nb);
+          if (feat < d) {
+            const float y = acc[mb][nb][r];
+            float q = rintf(__fmul_rn(y, rinv));
+            q = fminf(fmaxf(q, -7.f), 7.f);
+            if (!(s > 0.f)) q = 0.f;
+            const float diff = y - q * s;
+            e2 = fmaf(diff, diff, e2);
+            y2 = fmaf(y, y, y2);
+            if (codes && tv) codes[((int64_t)batch * n_tokens + token) * d + feat] = (int8_t)q;
+          }
+        }
+        if (err_part) {
+#pragma unroll
+          for (int o = 16; o >= 1; o >>= 1) {
+            e2 += __shfl_xor(e2, o);
+            y2 += __shfl_xor(y2, o);
+          }
+          if ((f.lane & 31) == 0 && tv)
+            err_part[((int64_t)batch * PN + pn) * n_tokens + token] = make_float2(e2, y2);
+        }
+      }
+    }
+  }
+};
+
+}  // namespace kt

@@ -1,0 +1,82 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol the
+header declares, sizes its workspace sensibly and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2503_01483_amd as kt
+from paper_2503_01483_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "kt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    L = kt.lib()
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_version_and_error_text():
+    assert kt.kt_version() >= 100
+    assert isinstance(kt.kt_last_error(), str)
+
+
+def test_workspace_bytes():
+    f = kt.kt_workspace_bytes
+    assert f(kt.KT_OP_LOSS_GRAD, 1, 2048, 256, kt.KT_F32) > 2 * 2048 * 256 * 4
+    big = f(kt.KT_OP_LOSS_GRAD, 1, 131072, 4096, kt.KT_BF16)
+    assert 2 * 2**30 < big < 3 * 2**30          # token-minor X and G copies dominate
+    assert f(kt.KT_OP_LOSS_GRAD, 1, 100, 100, kt.KT_BF16) == 0   # d not a multiple of 128
+    assert f(kt.KT_OP_LOSS_GRAD, 0, 100, 128, kt.KT_BF16) == 0
+    assert f(kt.KT_OP_CAYLEY, 1, 0, 4096, kt.KT_F32) >= 5 * 4096 * 4096 * 4
+    assert f(kt.KT_OP_FAKEQUANT, 2, 1000, 128, kt.KT_BF16) > 0
+    assert f(99, 1, 10, 128, kt.KT_BF16) == 0
+    # monotone in n
+    assert f(kt.KT_OP_LOSS_GRAD, 1, 4096, 256, kt.KT_BF16) > f(kt.KT_OP_LOSS_GRAD, 1, 1024, 256, kt.KT_BF16)
+
+
+def test_argument_errors_are_synchronous():
+    L = kt.lib()
+    fake = ctypes.c_void_p(4096)  # never dereferenced: every call below fails its checks first
+    ws = ctypes.c_void_p(1 << 20)
+    st = L.kt_kurtosis_loss_grad(None, 128, fake, 128, 1, 16, 128, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 1 and "null" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, 100, fake, 100, 1, 16, 100, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 2 and "multiple of 128" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, 132, fake, 128, 1, 16, 128, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 2 and "ldx" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, 128, fake, 128, 1, 16, 128, 0, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 3
+    st = L.kt_kurtosis_loss_grad(fake, 128, fake, 128, 1, 16, 128, 7, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 3
+    st = L.kt_kurtosis_loss_grad(fake, 128, fake, 128, 1, 16, 128, 1, 1, 0.0, fake, None, None, ws, 16, None)
+    assert st == 4 and "workspace" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, 128, fake, 128, 1, 16, 128, 1, 1, -1.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 1
+    st = L.kt_cayley_step(None, fake, None, 1, 128, 0.01, None, None, ws, 1 << 30, None)
+    assert st == 1
+    st = L.kt_cayley_step(fake, fake, None, 1, 64, 0.01, None, None, ws, 1 << 30, None)
+    assert st == 2
+    st = L.kt_cayley_step(fake, fake, None, 1, 128, float("nan"), None, None, ws, 1 << 30, None)
+    assert st == 1
+    st = L.kt_rotate_fakequant_int4(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.5, None, fake, None, None, ws, 1 << 30, None)
+    assert st == 1 and "clip" in kt.kt_last_error()
+    st = L.kt_rotate_fakequant_int4(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.0, None, None, None, None, ws, 1 << 30, None)
+    assert st == 1
+    # a good call clears the text only when it runs; bad ones leave their own message
+    assert kt.kt_last_error() != ""
+
+
+def test_binding_has_no_fallback():
+    src = open(os.path.join(ROOT, "paper_2503_01483_amd", "binding.py")).read()
+    assert "oracle" not in src

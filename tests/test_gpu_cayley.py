@@ -1,0 +1,86 @@
+"""GPU parity: kt_cayley_step through the C ABI against the oracle's exact (LU) Cayley step."""
+import numpy as np
+import pytest
+import torch
+
+import ktgen
+import oracle
+import paper_2503_01483_amd as kt
+from parity_util import rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(R, G, lr, want_lowp=True):
+    Rd = R.clone().cuda().contiguous()
+    Gd = G.cuda().contiguous()
+    b, d = Rd.shape[0], Rd.shape[-1]
+    lowp = torch.zeros((b, d, d), dtype=torch.bfloat16, device="cuda") if want_lowp else None
+    oe = torch.full((b,), float("nan"), device="cuda")
+    info = torch.zeros((b,), dtype=torch.int32, device="cuda")
+    kt.kt_cayley_step(Rd, Gd, lr, R_lowp=lowp, ortho_err=oe, info=info)
+    torch.cuda.synchronize()
+    return Rd.cpu(), None if lowp is None else lowp.cpu(), oe.cpu().numpy(), info.cpu().numpy()
+
+
+@pytest.mark.parametrize("d,batch,lr,gscale", [(128, 1, 1e-2, 1.0), (128, 3, 0.05, 1.0), (256, 1, 1e-2, 3.0),
+                                                (384, 2, 1e-3, 10.0), (512, 1, 1e-2, 1.0)])
+def test_against_oracle(d, batch, lr, gscale):
+    g = torch.Generator().manual_seed(d + batch)
+    R = torch.stack([ktgen.random_orthogonal(d, seed=b) for b in range(batch)])
+    G = torch.randn((batch, d, d), generator=g) * gscale / np.sqrt(d)
+    Rn, lowp, oe, info = _run(R, G, lr)
+    for b in range(batch):
+        ref = oracle.cayley_step(ktgen.to_f64(R[b]), ktgen.to_f64(G[b]), lr)
+        step = ref - ktgen.to_f64(R[b])
+        assert rel_fro(Rn[b].numpy().astype(np.float64) - ktgen.to_f64(R[b]), step) <= 1e-4
+        RtR = Rn[b].double().T @ Rn[b].double()
+        assert float((RtR - torch.eye(d, dtype=torch.float64)).abs().max()) < 1e-6
+        # the library's own figure is an fp32 GEMM: true value plus a few ulp of 1
+        assert oe[b] < 1e-6 and abs(oe[b] - float((RtR - torch.eye(d, dtype=torch.float64)).abs().max())) < 6e-7
+        assert 1 <= info[b] <= 48
+    assert torch.equal(lowp, Rn.to(torch.bfloat16))
+
+
+def test_zero_step_and_radial_gradient():
+    d = 128
+    R = ktgen.random_orthogonal(d, seed=4).unsqueeze(0)
+    G = torch.randn((1, d, d), generator=torch.Generator().manual_seed(1))
+    Rn, _, _, info = _run(R, G, 0.0)
+    assert torch.equal(Rn, R) and info[0] == 1
+    S = G[0] + G[0].T
+    Rn, _, _, _ = _run(R, (R[0] @ S).unsqueeze(0), 0.01)     # A = R S R^T - R S R^T = 0
+    assert float((Rn - R).abs().max()) < 1e-6
+
+
+def test_divergent_step_is_flagged_not_hung():
+    # (lr/2)||A|| >> 1: the fixed point does not contract; the library must say so
+    d = 128
+    R = torch.eye(d).unsqueeze(0)
+    G = torch.randn((1, d, d), generator=torch.Generator().manual_seed(2))
+    _, _, _, info = _run(R, G, 10.0)
+    assert info[0] == -1
+
+
+def test_teacher_forced_steps_c1():
+    # three consecutive loss+grad+Cayley steps on the Tiny config; at every step the GPU starts
+    # from the oracle's R so that chaotic drift cannot build up
+    X, R, cfg = ktgen.make_problem("C1", seed=0, n=1024)
+    Xd = X.cuda()
+    Xo = ktgen.to_f64(X[0])
+    Ro = ktgen.to_f64(R[0])
+    losses = []
+    for _ in range(3):
+        o = oracle.loss_grad(Xo, Ro)
+        Rd = torch.tensor(Ro, dtype=torch.float32).unsqueeze(0).cuda()
+        dR = torch.empty_like(Rd)
+        loss = kt.kt_kurtosis_loss_grad(Xd, Rd, dR=dR)
+        kt.kt_cayley_step(Rd, dR, cfg["lr"] * 50)
+        torch.cuda.synchronize()
+        Rnext = oracle.cayley_step(Ro, o["dR"], cfg["lr"] * 50)
+        assert abs(loss.item() - o["loss"]) <= 1e-4 * o["loss"]
+        assert rel_fro(dR[0].cpu().numpy(), o["dR"]) <= 1e-4
+        assert rel_fro(Rd[0].cpu().numpy().astype(np.float64) - Ro, Rnext - Ro) <= 2e-4
+        losses.append(o["loss"])
+        Ro = Rnext
+    assert losses[2] < losses[0]

@@ -1,0 +1,137 @@
+"""GPU parity: kt_kurtosis_loss_grad through the C ABI against the fp64 oracle.
+
+Tolerances: relative 1e-4 on the fp32 path, 2e-2 on the bf16 path (loss: |dL|/|L|;
+per-row kurtosis: max relative; dR: Frobenius relative), as the benchmark definition
+states.  Inputs are the seeded synthetic activations of ktgen.
+"""
+import numpy as np
+import pytest
+import scipy.linalg
+import torch
+
+import ktgen
+import paper_2503_01483_amd as kt
+from parity_util import check_loss_grad, gpu_loss_grad, oracle_loss_grad, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+
+
+def test_c1_tiny_fp32_full():
+    X, R, cfg = ktgen.make_problem("C1", seed=0)
+    g = gpu_loss_grad(X, R)
+    o = oracle_loss_grad(X, R)
+    check_loss_grad(g, o, TOL_F32)
+
+
+@pytest.mark.parametrize("n,d", [(1, 128), (63, 128), (64, 256), (65, 128), (257, 384), (1000, 256)])
+def test_fp32_ragged_shapes(n, d):
+    X = ktgen.make_x(n, d, seed=n + d, outlier_cols=3, outlier_scale=30.0, t_frac=0.05, dtype="f32")
+    R = ktgen.random_orthogonal(d, seed=d)
+    check_loss_grad(gpu_loss_grad(X, R), oracle_loss_grad(X, R), TOL_F32)
+
+
+@pytest.mark.parametrize("n,d,batch", [(1, 128, 1), (200, 128, 3), (777, 256, 1), (1000, 384, 2),
+                                        (520, 512, 1), (2048, 768, 1), (300, 1024, 1)])
+def test_bf16_shapes(n, d, batch):
+    xs = [ktgen.make_x(n, d, seed=7 * b + n, outlier_cols=4, outlier_scale=60.0, t_frac=0.05,
+                       dtype="bf16") for b in range(batch)]
+    rs = [ktgen.random_orthogonal(d, seed=b + d) if b % 2 == 0 else torch.eye(d) for b in range(batch)]
+    X, R = torch.stack(xs), torch.stack(rs)
+    check_loss_grad(gpu_loss_grad(X, R), oracle_loss_grad(X, R), TOL_BF16)
+
+
+def test_bf16_accepts_bf16_rotation_and_row_stride():
+    n, d = 333, 256
+    Xfull = ktgen.make_x(n, d + 64, seed=5, outlier_cols=4, outlier_scale=60.0, dtype="bf16").cuda()
+    X = Xfull[:, :d]                       # ldx = d + 64
+    R = ktgen.random_orthogonal(d, seed=9)
+    o = oracle_loss_grad(X.cpu().contiguous(), R)
+    g32 = gpu_loss_grad(X.unsqueeze(0), R.unsqueeze(0))
+    g16 = gpu_loss_grad(X.unsqueeze(0), R.to(torch.bfloat16).unsqueeze(0))
+    check_loss_grad(g32, o, TOL_BF16)
+    assert np.array_equal(g32["dR"], g16["dR"]) and np.array_equal(g32["loss"], g16["loss"])
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", TOL_F32), ("bf16", TOL_BF16)])
+def test_target_loss(dtype, tol):
+    n, d = 512, 256
+    X = ktgen.make_x(n, d, seed=11, outlier_cols=2, outlier_scale=5.0, dtype=dtype)
+    X[::2] = (torch.rand(n // 2, d) * 2 - 1).to(X.dtype)     # rows on both sides of the target
+    R = torch.eye(d)
+    o = oracle_loss_grad(X, R, kappa_target=2.4)
+    assert (o["row_kurt"] > 2.4).any() and (o["row_kurt"] < 2.4).any()
+    check_loss_grad(gpu_loss_grad(X, R, kappa_target=2.4), o, tol)
+
+
+def test_loss_only_skips_gradient():
+    X, R, _ = ktgen.make_problem("C1", seed=1, n=500)
+    g = gpu_loss_grad(X, R, want_dR=False, want_rows=False)
+    o = oracle_loss_grad(X, R, want_dR=False)
+    assert abs(g["loss"][0] - o["loss"][0]) <= TOL_F32 * o["loss"][0]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_and_minimum_rows(dtype):
+    # one-hot rows through a Hadamard rotation: e_0 -> constant row (no spread: kappa := 0,
+    # no gradient), e_k -> +-1/sqrt(d) row with kappa = 1 exactly and zero gradient
+    d = 256
+    H = torch.tensor(scipy.linalg.hadamard(d) / np.sqrt(d), dtype=torch.float32)
+    X = torch.eye(d)[:130].to(torch.bfloat16 if dtype == "bf16" else torch.float32)
+    X[129] = 0  # an all-zero row
+    g = gpu_loss_grad(X, H)
+    o = oracle_loss_grad(X, H)
+    assert g["row_kurt"][0, 0] == 0.0 and g["row_kurt"][0, 129] == 0.0
+    assert np.allclose(g["row_kurt"][0, 1:129], 1.0, atol=1e-5)
+    assert np.allclose(g["row_kurt"], o["row_kurt"], atol=1e-5)
+    assert abs(g["loss"][0] - o["loss"][0]) < 1e-5
+    assert np.abs(g["dR"]).max() < 1e-6 and np.abs(o["dR"]).max() < 1e-12
+
+
+def test_deterministic_and_workspace_reuse():
+    X, R, _ = ktgen.make_problem("C2", seed=3, n=3000)
+    ws = kt.Workspace()
+    a = gpu_loss_grad(X, R, ws=ws)
+    junk = ws.buf
+    junk.fill_(0xFF)                        # stale scratch must not matter
+    b = gpu_loss_grad(X, R, ws=ws)
+    assert np.array_equal(a["dR"], b["dR"]) and np.array_equal(a["loss"], b["loss"])
+    assert np.array_equal(a["row_kurt"], b["row_kurt"])
+
+
+def test_invariants_row_permutation_and_identities():
+    n, d = 4096, 512
+    X = ktgen.make_x(n, d, seed=21, outlier_cols=8, outlier_scale=100.0, t_frac=0.05, dtype="bf16")
+    R = ktgen.random_orthogonal(d, seed=22)
+    g = gpu_loss_grad(X, R)
+    dR = g["dR"][0].astype(np.float64)
+    Rb = ktgen.to_f64(ktgen.bf16_round(R))
+    nrm = np.linalg.norm(dR)
+    # shift / scale invariance of kurtosis: dR 1 = 0 and <dR, R> = 0 at the rounded R
+    assert np.linalg.norm(dR.sum(1)) <= 1e-3 * nrm * np.sqrt(d)
+    assert abs((dR * Rb).sum()) <= 1e-3 * nrm * np.linalg.norm(Rb)
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(1))
+    gp = gpu_loss_grad(X[perm], R)
+    assert np.allclose(gp["row_kurt"][0], g["row_kurt"][0][perm.numpy()], rtol=1e-5)
+    assert rel_fro(gp["dR"][0], g["dR"][0]) < 1e-4
+    assert abs(gp["loss"][0] - g["loss"][0]) <= 1e-5 * g["loss"][0]
+
+
+def test_c2_shape_chunk_vs_oracle_and_additivity():
+    # C2 recipe at its real d = 2048 (R = I start), GPU vs oracle on a chunk the oracle can do,
+    # and GPU(all rows) against the n-weighted sum of GPU(chunks)
+    X, R, cfg = ktgen.make_problem("C2", seed=0, n=2560)
+    d = cfg["d"]
+    chunk = slice(0, 512)
+    check_loss_grad(gpu_loss_grad(X[:, chunk], R), oracle_loss_grad(X[:, chunk], R), TOL_BF16)
+    full = gpu_loss_grad(X, R)
+    acc = np.zeros((d, d))
+    lacc = 0.0
+    for lo in range(0, 2560, 640):
+        part = gpu_loss_grad(X[:, lo:lo + 640], R)
+        acc += 640 * part["dR"][0].astype(np.float64)
+        lacc += 640 * part["loss"][0]
+    assert rel_fro(2560 * full["dR"][0], acc) < 5e-3      # bf16 rounding of dL/dY differs per 1/n
+    assert abs(2560 * full["loss"][0] - lacc) <= 1e-5 * lacc
