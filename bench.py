@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark of the KurTail rotation-learning step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic calibration
+activations resident in HBM: kt_kurtosis_loss_grad (forward GEMM + row moments, row
+finalisation, backward recompute GEMM, X^T G GEMM) followed by kt_cayley_step.
+Prints ONE JSON line: tokens/s for the whole step, the roofline figures of the dominant
+kernel measured with HIP events inside the timed region, and the fp64 CPU oracle timed on
+a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # MI355X fp32 matrix
+KERNEL_NAMES = {0: "gemm_nt_kernel<bf16 256x256, EpiMoments> (forward + row moments)",
+                1: "gemm_nt_kernel<bf16 256x256, EpiGrad> (recompute + dL/dY)",
+                2: "gemm_nt_kernel<bf16 256x256, EpiStore> (dR = X^T G)"}
+CPU_SAMPLE_ROWS = {"C1": 2048, "C2": 32768, "C3": 16384, "C4": 131072, "C5": 4096}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C3", help="workload: C1..C5 (default C3: d=4096, n=131072)")
+    ap.add_argument("--n", type=int, default=None, help="override the token count (debugging)")
+    ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (token rows would shard over "
+              "GPUs with one all-reduce of dR per step, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import ktgen
+    import paper_2503_01483_amd as kt
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    t0 = time.time()
+    X, R, cfg = ktgen.make_problem(args.config, seed=0, device=dev, n=args.n, batch=args.batch)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    batch, n, d = X.shape
+    lr = cfg["lr"]
+    bf16 = cfg["dtype"] == "bf16"
+
+    ws = kt.Workspace(dev)
+    ws.get(max(kt.kt_workspace_bytes(kt.KT_OP_LOSS_GRAD, batch, n, d, kt.KT_BF16 if bf16 else kt.KT_F32),
+               kt.kt_workspace_bytes(kt.KT_OP_CAYLEY, batch, 0, d, kt.KT_F32)))
+    loss = torch.zeros(batch, device=dev)
+    dR = torch.empty((batch, d, d), device=dev)
+    info = torch.zeros(batch, dtype=torch.int32, device=dev)
+    Rw = R.clone()
+
+    def step():
+        kt.kt_kurtosis_loss_grad(X, Rw, loss=loss, dR=dR, workspace=ws)
+        if not args.no_cayley:
+            kt.kt_cayley_step(Rw, dR, lr, info=info, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    loss_first = loss.clone()
+    kt.kt_profile_enable(8 * args.steps + 8)
+    kt.kt_profile_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = {k: kt.kt_profile_read(k) for k in range(5)}
+    kt.kt_profile_enable(0)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = batch * n * args.steps / elapsed
+    flops_launch = 2.0 * batch * n * d * d           # one GEMM launch: 2 n d^2 per problem
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    kern = {}
+    for k in (0, 1, 2):
+        tot, cnt = prof[k]
+        if cnt:
+            kern[k] = {"avg_ms": tot / cnt, "launches": cnt, "tflops": flops_launch / (tot / cnt * 1e-3) / 1e12}
+    dom = max(kern, key=lambda k: kern[k]["avg_ms"])
+    roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom] if bf16 else "gemm_nt_kernel<f32 128x128>",
+                "achieved": round(kern[dom]["tflops"], 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(kern[dom]["tflops"] / peak, 4), "avg_launch_ms": round(kern[dom]["avg_ms"], 4),
+                "flops_per_launch": flops_launch, "traffic": None}
+    breakdown = {"fwd_moments_ms": round(kern[0]["avg_ms"], 4), "bwd_recompute_ms": round(kern[1]["avg_ms"], 4),
+                 "grad_xtg_ms": round(kern[2]["avg_ms"], 4),
+                 "x_transpose_ms": round(prof[3][0] / max(prof[3][1], 1), 4),
+                 "cayley_ms": round(prof[4][0] / max(prof[4][1], 1), 4),
+                 "cayley_iters_last": info.cpu().tolist()[:4]}
+    alg_tflops = 4.0 * batch * n * d * d * args.steps / elapsed / 1e12
+    hw_tflops = 6.0 * batch * n * d * d * args.steps / elapsed / 1e12
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        rows = min(n, CPU_SAMPLE_ROWS[args.config])
+        Xs = ktgen.to_f64(X[0, :rows])
+        Rs = ktgen.to_f64(ktgen.bf16_round(R[0]) if bf16 else R[0])
+        t0 = time.perf_counter()
+        o = oracle.loss_grad(Xs, Rs)
+        cpu_s = time.perf_counter() - t0
+        cpu = {"value": round(rows / cpu_s, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"plain fp64 oracle loss+grad on the first {rows} token rows of problem 0 at d={d} "
+                         f"({cpu_s:.1f} s); Cayley step not included; not a tuned CPU baseline"}
+        # while the oracle result is here: the same rows through the GPU path must agree
+        l2 = torch.zeros(1, device=dev)
+        d2 = torch.empty((1, d, d), device=dev)
+        kt.kt_kurtosis_loss_grad(X[0:1, :rows], R[0:1], loss=l2, dR=d2, workspace=ws)
+        torch.cuda.synchronize()
+        rel = float(np.linalg.norm(d2[0].cpu().numpy() - o["dR"]) / np.linalg.norm(o["dR"]))
+        cpu["gpu_vs_oracle_on_sample"] = {"loss_rel": abs(l2.item() - o["loss"]) / o["loss"], "dR_rel": rel}
+
+    out = {
+        "metric": "calibration tokens/sec through kurtosis loss+grad step; % of bf16 MFMA peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: n={n} tokens x d={d}, batch={batch}, "
+                               f"loss+grad{'' if args.no_cayley else '+Cayley'} step, lr={lr}",
+                   "global_batch": batch * n, "hidden": d},
+        "tflops_algorithmic_4nd2": round(alg_tflops, 2), "tflops_hardware_6nd2": round(hw_tflops, 2),
+        "frac_of_bf16_peak_algorithmic": round(alg_tflops / peak, 4),
+        "roofline": roofline, "kernels_ms": breakdown, "cpu_baseline": cpu,
+        "loss_first_last": [float(loss_first[0]), float(loss[0])], "input_gen_s": round(gen_s, 1),
+        "context": "paper: SpinQuant needs >= 4x H100 80GB for Llama3-70B rotations, KurTail a single GPU",
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

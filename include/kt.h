@@ -143,6 +143,24 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
                                    float* err, void* workspace, size_t workspace_bytes,
                                    void* stream);
 
+/*
+ * Measurement aid (not part of the method; off by default).  When enabled, the
+ * library brackets its large launches with HIP events on the caller's stream so a
+ * benchmark can read per-kernel durations without a profiler attached.  This is the
+ * only process-global state the library has; enable/disable/read are host calls and
+ * must not run concurrently with other library calls.
+ *   kernel ids: 0 forward GEMM + row moments, 1 backward recompute GEMM + dL/dY,
+ *               2 gradient GEMM X^T G, 3 token-minor copy of X,
+ *               4 every launch of kt_cayley_step, 5 every launch of kt_rotate_fakequant_int4
+ * kt_profile_enable(max_records): records up to max_records bracketed launches (0 turns
+ *   profiling off and releases the events).
+ * kt_profile_read(id, &total_ms, &launches): waits for the recorded events of that id and
+ *   returns their summed duration and count; kt_profile_reset() forgets all records.
+ */
+kt_status kt_profile_enable(int32_t max_records);
+kt_status kt_profile_read(int32_t kernel_id, double* total_ms, int32_t* launches);
+kt_status kt_profile_reset(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,4 +21,7 @@ from .binding import (  # noqa: F401
     kt_cayley_step,
     kt_rotate_fakequant_int4,
     Workspace,
+    kt_profile_enable,
+    kt_profile_read,
+    kt_profile_reset,
 )

@@ -12,7 +12,8 @@ KT_F32, KT_BF16 = 0, 1
 KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT = 0, 1, 2
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_cayley_step", "kt_rotate_fakequant_int4")
+           "kt_cayley_step", "kt_rotate_fakequant_int4", "kt_profile_enable", "kt_profile_read",
+           "kt_profile_reset")
 
 
 class KtError(RuntimeError):
@@ -50,6 +51,12 @@ def lib():
     L.kt_rotate_fakequant_int4.restype = i32
     L.kt_rotate_fakequant_int4.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32,
                                            vp, vp, vp, vp, vp, sz, vp]
+    L.kt_profile_enable.restype = i32
+    L.kt_profile_enable.argtypes = [i32]
+    L.kt_profile_read.restype = i32
+    L.kt_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    L.kt_profile_reset.restype = i32
+    L.kt_profile_reset.argtypes = []
     _lib = L
     return L
 
@@ -153,3 +160,18 @@ def kt_rotate_fakequant_int4(X, R, *, clip_ratio=1.0, scales_in=None, scales_out
                                           _dtype_code(R), float(clip_ratio), _ptr(scales_in),
                                           _ptr(scales_out), _ptr(codes), _ptr(err), _ptr(ws),
                                           ws.numel(), _stream(stream)))
+
+
+def kt_profile_enable(max_records):
+    _check(lib().kt_profile_enable(int(max_records)))
+
+
+def kt_profile_reset():
+    _check(lib().kt_profile_reset())
+
+
+def kt_profile_read(kernel_id):
+    """(total_ms, launches) of the bracketed launches with this id since the last reset."""
+    tot, cnt = ctypes.c_double(0.0), ctypes.c_int32(0)
+    _check(lib().kt_profile_read(int(kernel_id), ctypes.byref(tot), ctypes.byref(cnt)))
+    return tot.value, cnt.value

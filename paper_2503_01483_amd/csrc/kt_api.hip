@@ -24,6 +24,27 @@ static kt_status fail(kt_status code, const char* fmt, ...) {
 
 static bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// ------------------------------------------------------------------ profiling -----
+// Optional event brackets around the large launches (see kt_profile_enable).
+struct ProfRecord { hipEvent_t start, stop; int id; };
+static ProfRecord* g_prof = nullptr;
+static int g_prof_cap = 0, g_prof_used = 0;
+
+struct ProfScope {
+  ProfRecord* rec = nullptr;
+  hipStream_t st;
+  ProfScope(int id, hipStream_t s) : st(s) {
+    if (g_prof && g_prof_used < g_prof_cap) {
+      rec = &g_prof[g_prof_used++];
+      rec->id = id;
+      (void)hipEventRecord(rec->start, st);
+    }
+  }
+  ~ProfScope() {
+    if (rec) (void)hipEventRecord(rec->stop, st);
+  }
+};
+
 // ------------------------------------------------------------------ tiles ---------
 using bf16 = __bf16;
 using TB_BIG = Tile<bf16, 256, 256, 2, 2>;   // d % 256 == 0
@@ -245,6 +266,7 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
 
   // a1: forward GEMM (features on m, tokens on n) with the moment epilogue
   {
+    ProfScope prof(0, st);
     EpiMoments<TFWD> e;
     e.part = part; e.n_tokens = (int)n; e.d = (int)d; e.P = p.P;
     if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
@@ -261,6 +283,7 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
 
   // token-minor copy of X for the last GEMM (zero padded to ldt tokens)
   {
+    ProfScope prof(3, st);
     dim3 grid((unsigned)(p.ldt / 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
     hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.ldt,
                        d * p.ldt, (int)n, (int)p.ldt, (int)d);
@@ -268,6 +291,7 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   }
   // a3: recompute Y, write dL/dY token-minor
   {
+    ProfScope prof(1, st);
     EpiGrad<TFWD> e;
     e.coef = coef; e.GT = GT; e.ldt = p.ldt; e.n_tokens = (int)n; e.d = (int)d;
     if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
@@ -275,6 +299,7 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   }
   // a4: dR = X^T G, split over tokens
   {
+    ProfScope prof(2, st);
     EpiStore<TDD> e;
     e.ldc = d; e.M = (int)d; e.N = (int)d;
     if (p.split_k > 1) {
@@ -411,6 +436,7 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   unsigned* delta = reinterpret_cast<unsigned*>(ws + p.o_delta);
   const int D = (int)d;
   const int64_t dd = d * d;
+  ProfScope prof(4, st);
 
   // M = dR R^T
   {
@@ -468,6 +494,7 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
   if (s != KT_OK) return s;
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope prof(5, st);
   if (p.fp32)
     return run_quant<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
                                     scales_out, codes, err, ws, st);
@@ -476,6 +503,50 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
                                            scales_out, codes, err, ws, st);
   return run_quant<bf16, TB_M128, TB_N128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
                                            scales_out, codes, err, ws, st);
+}
+
+kt_status kt_profile_reset(void) {
+  g_prof_used = 0;
+  return KT_OK;
+}
+
+kt_status kt_profile_enable(int32_t max_records) {
+  g_err[0] = 0;
+  if (max_records < 0) return fail(KT_ERR_INVALID_ARG, "max_records must be >= 0");
+  for (int i = 0; i < g_prof_cap; ++i) {
+    (void)hipEventDestroy(g_prof[i].start);
+    (void)hipEventDestroy(g_prof[i].stop);
+  }
+  delete[] g_prof;
+  g_prof = nullptr;
+  g_prof_cap = g_prof_used = 0;
+  if (max_records == 0) return KT_OK;
+  g_prof = new ProfRecord[max_records];
+  for (int i = 0; i < max_records; ++i) {
+    if (hipEventCreate(&g_prof[i].start) != hipSuccess || hipEventCreate(&g_prof[i].stop) != hipSuccess)
+      return fail(KT_ERR_DEVICE, "hipEventCreate failed");
+    g_prof_cap = i + 1;
+  }
+  return KT_OK;
+}
+
+kt_status kt_profile_read(int32_t kernel_id, double* total_ms, int32_t* launches) {
+  g_err[0] = 0;
+  if (!total_ms || !launches) return fail(KT_ERR_INVALID_ARG, "outputs must not be null");
+  double tot = 0.0;
+  int cnt = 0;
+  for (int i = 0; i < g_prof_used; ++i) {
+    if (g_prof[i].id != kernel_id) continue;
+    if (hipEventSynchronize(g_prof[i].stop) != hipSuccess) return fail(KT_ERR_DEVICE, "event sync failed");
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof[i].start, g_prof[i].stop) != hipSuccess)
+      return fail(KT_ERR_DEVICE, "event elapsed failed");
+    tot += ms;
+    ++cnt;
+  }
+  *total_ms = tot;
+  *launches = cnt;
+  return KT_OK;
 }
 
 }  // extern "C"
