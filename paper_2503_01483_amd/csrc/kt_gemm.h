@@ -16,11 +16,13 @@
 // accumulate in registers with no cross-lane traffic until one final shuffle.
 //
 // LDS: each stage holds BM + BN rows of 128 bytes of K; 16-byte chunks are
-// XOR-swizzled with the row so both the 16-byte stores and the MFMA fragment reads
-// are bank-conflict free.  Two stages, register prefetch of the next K slab.
+// XOR-swizzled with the row pair so both the 16-byte stores and the MFMA fragment
+// reads are bank-conflict free.  Two stages, register prefetch of the next K slab.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace kt {
 
@@ -74,8 +76,13 @@ struct Tile {
   static_assert(NT % kChunks == 0, "thread count must be a multiple of 8");
 };
 
+// LDS has 64 banks of 4 bytes: two 128-byte tile rows share one bank window, and a
+// 16-byte access is served 16 lanes at a time.  XOR-ing the chunk index with (row >> 1)
+// makes 16 consecutive rows at the same logical chunk hit 16 distinct 16-byte slots of
+// the 256-byte window (measured: 194 B/clk/CU, against 122 with a plain row & 7 key).
+__device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & (kChunks - 1); }
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * kRowBytes + (((chunk ^ row) & (kChunks - 1)) << 4);
+  return row * kRowBytes + ((chunk ^ swizzle_key(row)) << 4);
 }
 
 // Geometry of one accumulator element, shared by every epilogue.
@@ -97,9 +104,46 @@ struct Frag {
   __device__ __forceinline__ int n_of(int nb) const { return wn * TL::WTN + nb * 32 + (lane & 31); }
 };
 
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+// Calls f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), fully unrolled.
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Wait for this wave's outstanding LDS operations only (vmcnt and expcnt left at their
+// maxima), then meet the other waves.  A full __syncthreads() would also drain the
+// global loads that are deliberately kept in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // Main loop.  Rows of A beyond M (and of B beyond N) are read from the last valid
 // row, so every load stays inside the operand; the epilogue masks them out.
-// The K range [k0, k0 + k_slabs*BK) must lie inside both operands' rows.
+// The K range [k0, k0 + k_slabs*BK) must lie inside both operands' rows, and
+// (BM-1)*lda*sizeof(T) + 128 (same for B) must fit 32 bits (the host checks this).
+//
+// Schedule.  One K slab = 4 sub-steps of MB*NB MFMA "slots".  Everything that is not
+// an MFMA is dealt out over the slots, one or two instructions behind each MFMA, and
+// pinned there with sched_barrier, so the matrix pipe never waits for a block of
+// memory instructions to issue:
+//   sub-steps 0-2: behind the first slots, read the fragments of the next sub-step;
+//                  spread over all their slots, write the NEXT slab (registers -> other
+//                  LDS stage) one 16-byte chunk at a time, and refill each freed
+//                  register with the same chunk of slab+2 from global memory
+//   sub-step 3:    barrier (LDS only), then read sub-step 0 of the next slab
+// The fragments of sub-step s+1 are therefore on their way a whole sub-step before
+// the MFMAs that use them, each global load a whole slab before its LDS store, and
+// neither the LDS nor the vector-memory path ever sees a burst (a burst of 16 stores
+// per wave made the matrix pipe wait ~1000 cycles per slab).
 template <class TL>
 __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__ A, int64_t lda,
                                               int M, int m0,
@@ -108,84 +152,141 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
                                               floatx16 (&acc)[TL::MB][TL::NB], char* lds) {
   using T = typename TL::T;
   constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
+  constexpr int MB = TL::MB, NB = TL::NB, NMMA = MB * NB, NFRAG = MB + NB;
+  constexpr int A_LD = TL::A_LD, B_LD = TL::B_LD, NLD = A_LD + B_LD;
+  constexpr int ROWS_PER_PASS = TL::NT / kChunks;
+  // LDS layout: [A stage 0][A stage 1][B stage 0][B stage 1]; every stage offset and
+  // every per-block row offset below is a compile-time immediate of the ds_ instruction.
+  constexpr int B_BASE = 2 * TL::A_BYTES;
+  static_assert(kChunks / 2 == 4, "the schedule is written for 4 K sub-steps per slab");
+  static_assert(ROWS_PER_PASS % 16 == 0, "swizzle key must not change between load passes");
+  static_assert(NFRAG <= NMMA && NLD <= 3 * NMMA, "not enough MFMA slots to hide the memory instructions");
+
   const int tid = threadIdx.x;
   const int lrow = tid >> 3;  // row handled by this thread in load pass 0
   const int lchunk = tid & 7;
-  constexpr int ROWS_PER_PASS = TL::NT / kChunks;
 
-  const T* ga[TL::A_LD];
-  const T* gb[TL::B_LD];
-  int sa[TL::A_LD], sb[TL::B_LD];
+  // global addressing: uniform 64-bit base (advanced per slab) + 32-bit byte offsets
+  const char* Ab = reinterpret_cast<const char*>(A + (int64_t)m0 * lda + k0);
+  const char* Bb = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb + k0);
+  uint32_t og[NLD];
 #pragma unroll
-  for (int i = 0; i < TL::A_LD; ++i) {
-    const int row = lrow + i * ROWS_PER_PASS;
-    int grow = m0 + row;
-    grow = grow < M ? grow : M - 1;
-    ga[i] = A + (int64_t)grow * lda + k0 + lchunk * EPC;
-    sa[i] = lds_off(row, lchunk);
+  for (int i = 0; i < A_LD; ++i) {
+    int row = lrow + i * ROWS_PER_PASS;
+    row = (m0 + row < M) ? row : (M - 1 - m0);
+    og[i] = (uint32_t)(((int64_t)row * lda + lchunk * EPC) * (int64_t)sizeof(T));
   }
 #pragma unroll
-  for (int i = 0; i < TL::B_LD; ++i) {
-    const int row = lrow + i * ROWS_PER_PASS;
-    int grow = n0 + row;
-    grow = grow < N ? grow : N - 1;
-    gb[i] = B + (int64_t)grow * ldb + k0 + lchunk * EPC;
-    sb[i] = TL::A_BYTES + lds_off(row, lchunk);
+  for (int i = 0; i < B_LD; ++i) {
+    int row = lrow + i * ROWS_PER_PASS;
+    row = (n0 + row < N) ? row : (N - 1 - n0);
+    og[A_LD + i] = (uint32_t)(((int64_t)row * ldb + lchunk * EPC) * (int64_t)sizeof(T));
   }
+  const int st_off = lds_off(lrow, lchunk);  // + i*ROWS_PER_PASS*128 per pass (same key)
 
   const Frag<TL> f;
-  // fragment read offsets for K sub-step 0; sub-step s flips chunk bits by (2s)
-  int fa[TL::MB], fb[TL::NB];
+  // fragment addresses: one per K sub-step and operand; blocks and stages are immediates
+  const int key = swizzle_key(f.lane & 31);
+  int fa_s[4], fb_s[4];
 #pragma unroll
-  for (int mb = 0; mb < TL::MB; ++mb) fa[mb] = (f.m_block(mb) + (f.lane & 31)) * kRowBytes;
-#pragma unroll
-  for (int nb = 0; nb < TL::NB; ++nb)
-    fb[nb] = TL::A_BYTES + (f.wn * TL::WTN + nb * 32 + (f.lane & 31)) * kRowBytes;
-  const int swz = f.lane & 7;  // row & 7 for every fragment row of this lane
-
-  intx4 ra[TL::A_LD], rb[TL::B_LD];
-  auto load_global = [&](int slab) {
-    const int64_t ko = (int64_t)slab * TL::BK;
-#pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) ra[i] = *reinterpret_cast<const intx4*>(ga[i] + ko);
-#pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) rb[i] = *reinterpret_cast<const intx4*>(gb[i] + ko);
-  };
-  auto store_lds = [&](int stage) {
-    char* base = lds + stage * TL::STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) *reinterpret_cast<intx4*>(base + sa[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) *reinterpret_cast<intx4*>(base + sb[i]) = rb[i];
-  };
-  auto compute = [&](int stage) {
-    const char* base = lds + stage * TL::STAGE_BYTES;
-#pragma unroll
-    for (int s = 0; s < kChunks / 2; ++s) {
-      const int coff = (((2 * s + f.half) ^ swz) & (kChunks - 1)) << 4;
-      intx4 av[TL::MB], bv[TL::NB];
-#pragma unroll
-      for (int mb = 0; mb < TL::MB; ++mb) av[mb] = *reinterpret_cast<const intx4*>(base + fa[mb] + coff);
-#pragma unroll
-      for (int nb = 0; nb < TL::NB; ++nb) bv[nb] = *reinterpret_cast<const intx4*>(base + fb[nb] + coff);
-#pragma unroll
-      for (int mb = 0; mb < TL::MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < TL::NB; ++nb) Mma<T>::run(av[mb], bv[nb], acc[mb][nb]);
-    }
-  };
-
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int slab = 0; slab < k_slabs; ++slab) {
-    const int cur = slab & 1;
-    const bool more = slab + 1 < k_slabs;
-    if (more) load_global(slab + 1);
-    compute(cur);
-    if (more) store_lds(cur ^ 1);
-    __syncthreads();
+  for (int s = 0; s < 4; ++s) {
+    const int coff = (((2 * s + f.half) ^ key) & (kChunks - 1)) << 4;
+    fa_s[s] = (f.wm * TL::WTM + (f.lane & 31)) * kRowBytes + coff;
+    fb_s[s] = B_BASE + (f.wn * TL::WTN + (f.lane & 31)) * kRowBytes + coff;
   }
+
+  intx4 rg[NLD];        // one K slab in flight from global memory
+  intx4 fr[2][NFRAG];   // MFMA fragments, double buffered: [buf][0..MB) = A, [MB..) = B
+
+  auto gload = [&](auto i_c, int slab) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_c)::value;
+    const char* base = (i < A_LD ? Ab : Bb) + (int64_t)slab * kRowBytes;
+    rg[i] = *reinterpret_cast<const intx4*>(base + og[i]);
+  };
+  auto lstore = [&](auto i_c, auto stage_c) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_c)::value;
+    constexpr int stage = decltype(stage_c)::value;
+    constexpr int off = i < A_LD ? stage * TL::A_BYTES + i * ROWS_PER_PASS * kRowBytes
+                                 : B_BASE + stage * TL::B_BYTES + (i - A_LD) * ROWS_PER_PASS * kRowBytes;
+    *reinterpret_cast<intx4*>(lds + st_off + off) = rg[i];
+  };
+  auto fread = [&](auto buf_c, auto i_c, auto stage_c, auto s_c) __attribute__((always_inline)) {
+    constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value;
+    constexpr int stage = decltype(stage_c)::value, s = decltype(s_c)::value;
+    if constexpr (i < MB)
+      fr[buf][i] = *reinterpret_cast<const intx4*>(lds + fa_s[s] + stage * TL::A_BYTES + i * 32 * kRowBytes);
+    else
+      fr[buf][i] = *reinterpret_cast<const intx4*>(lds + fb_s[s] + stage * TL::B_BYTES + (i - MB) * 32 * kRowBytes);
+  };
+  auto mma = [&](auto buf_c, auto j_c) __attribute__((always_inline)) {
+    constexpr int buf = decltype(buf_c)::value, j = decltype(j_c)::value;
+    Mma<T>::run(fr[buf][j / NB], fr[buf][MB + j % NB], acc[j / NB][j % NB]);
+  };
+  using C0 = std::integral_constant<int, 0>;
+
+  // One slab.  PAR: parity of the slab (LDS stage).  The body is the same for every
+  // slab, so that the compiler sees one loop and no accumulator-carrying branches: near
+  // the end of K the "slab+2" request is clamped to the last slab (a redundant, in-bounds
+  // load) and the last slab's LDS store / fragment read move data nobody uses.
+  auto one_slab = [&](auto par_c, int slab) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par_c)::value;
+    constexpr bool MORE = true, LOAD2 = true;
+    using Cur = std::integral_constant<int, PAR>;
+    using Nxt = std::integral_constant<int, PAR ^ 1>;
+    const int slab2 = slab + 2 < k_slabs ? slab + 2 : k_slabs - 1;
+    static_for<4 * NMMA>([&](auto g_c) __attribute__((always_inline)) {
+      constexpr int g = decltype(g_c)::value;  // slot index inside the slab
+      constexpr int s = g / NMMA, j = g % NMMA;
+      using Buf = std::integral_constant<int, s & 1>;
+      using NBuf = std::integral_constant<int, (s + 1) & 1>;
+#ifndef KT_EXP_NOBARRIER
+      if constexpr (g == 3 * NMMA && MORE) lds_barrier();
+#endif
+      mma(Buf{}, std::integral_constant<int, j>{});
+      // fragments of the next sub-step: one LDS read behind each of the first slots
+      static_for<NFRAG>([&](auto i_c) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_c)::value;
+        if constexpr (i == j) {
+#ifndef KT_EXP_NOFREAD
+          if constexpr (s < 3) fread(NBuf{}, i_c, Cur{}, std::integral_constant<int, (s + 1) & 3>{});
+          else if constexpr (MORE) fread(NBuf{}, i_c, Nxt{}, C0{});
+#endif
+        }
+      });
+      // next slab: registers -> other LDS stage, spread evenly over the three sub-steps
+      // before the barrier; the freed register is refilled at once with slab+2
+      static_for<NLD>([&](auto i_c) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_c)::value;
+        if constexpr (i * 3 * NMMA / NLD == g) {
+#ifndef KT_EXP_NOLSTORE
+          if constexpr (MORE) lstore(i_c, Nxt{});
+#endif
+#ifndef KT_EXP_NOGLOAD
+          if constexpr (LOAD2) gload(i_c, slab2);
+#endif
+        }
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+  using P0 = std::integral_constant<int, 0>;
+  using P1 = std::integral_constant<int, 1>;
+
+  // prologue: slab 0 -> LDS stage 0, slab 1 -> registers, first fragments -> buffer 0
+  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { gload(i_c, 0); });
+  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { lstore(i_c, P0{}); });
+  const int slab1 = k_slabs > 1 ? 1 : 0;
+  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { gload(i_c, slab1); });
+  lds_barrier();
+  static_for<NFRAG>([&](auto i_c) __attribute__((always_inline)) { fread(P0{}, i_c, P0{}, C0{}); });
+  __builtin_amdgcn_sched_barrier(0);
+
+  int slab = 0;
+  for (; slab + 1 < k_slabs; slab += 2) {
+    one_slab(P0{}, slab);
+    one_slab(P1{}, slab + 1);
+  }
+  if (slab < k_slabs) one_slab(P0{}, slab);
 }
 
 // Launch description of one batched NT GEMM.
