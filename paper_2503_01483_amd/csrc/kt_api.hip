@@ -60,7 +60,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
 constexpr int kNumCUs = 256;
-constexpr int kCayleyMaxIters = 48;
+constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
 
 template <class TL, class Epi>
@@ -156,19 +156,27 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
 }
 
 struct CayleyPlan {
+  bool split;  // three-term bf16 GEMMs on the bf16 matrix cores instead of fp32 MFMA
   size_t o_m, o_b, o_rt, o_zt, o_u0, o_u1, o_delta, total;
 };
+
+// Large problems run their d^3 GEMMs as three-term bf16 products (about 2^-17 relative
+// per term, 3x the flops at ~16x the rate of the fp32 matrix pipe); small ones, where the
+// step costs microseconds anyway, stay in fp32.
+static bool cayley_use_split(int64_t d) { return d >= 1024 && d % 256 == 0; }
 
 static CayleyPlan plan_cayley(int64_t batch, int64_t d) {
   CayleyPlan p;
   Carver c;
+  p.split = cayley_use_split(d);
   const size_t mat = (size_t)batch * d * d * 4;
-  p.o_m = c.take(mat);  // M = dR R^T, later reused as the second U buffer
-  p.o_b = c.take(mat);
+  const size_t smat = (size_t)batch * d * d * 6;  // [d][3d] bf16
+  p.o_m = c.take(mat);  // M = dR R^T; in the fp32 path later reused as the second U buffer
+  p.o_b = c.take(p.split ? smat : mat);
   p.o_rt = c.take(mat);
   p.o_zt = c.take(mat);
-  p.o_u0 = c.take(mat);
-  p.o_u1 = p.o_m;
+  p.o_u0 = c.take(p.split ? smat : mat);
+  p.o_u1 = p.split ? c.take(smat) : p.o_m;
   p.o_delta = c.take((size_t)batch * kCayleyMaxIters * 4);
   p.total = c.off;
   return p;
@@ -441,6 +449,38 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   const int64_t dd = d * d;
   ProfScope prof(4, st);
 
+  if (p.split) {
+    // three-term bf16 path: operands live as [d][3d] bf16
+    __bf16* Bs = reinterpret_cast<__bf16*>(ws + p.o_b);
+    __bf16* Us[2] = {reinterpret_cast<__bf16*>(ws + p.o_u0), reinterpret_cast<__bf16*>(ws + p.o_u1)};
+    const int64_t sd = 3 * d * d;
+    const unsigned sb = (unsigned)(ceil_div(dd, 256) < 8192 ? ceil_div(dd, 256) : 8192);
+    // M = dR R^T with dR as [hi|hi|lo] (in Us[0]) and R as [hi|lo|hi] (in Us[1])
+    hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, dR, D, D, Us[0], 0);
+    hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, R, D, D, Us[1], 1);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "split launch failed");
+    {
+      EpiStore<TB_BIG> e;
+      e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
+      if (!launch_gemm<TB_BIG>(Us[0], 3 * d, sd, D, Us[1], 3 * d, sd, D, 3 * d, 0, (int)batch, e, st))
+        return fail(KT_ERR_DEVICE, "dR R^T GEMM launch failed");
+    }
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, delta, batch * kCayleyMaxIters, 0u);
+    hipLaunchKernelGGL(cayley_setup_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Mm, R,
+                       D, 0.5f * lr, (float*)nullptr, Rt, Zt, (float*)nullptr, Bs, Us[0]);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley set-up launch failed");
+    const unsigned ub = (unsigned)(ceil_div(dd / 4, 256) < 2048 ? ceil_div(dd / 4, 256) : 2048);
+    for (int it = 0; it < kCayleyMaxIters; ++it) {
+      EpiCayleyProduct<TB_BIG> e;
+      e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
+      e.delta = delta; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
+      if (!launch_gemm<TB_BIG>(Us[it & 1], 3 * d, sd, D, Bs, 3 * d, sd, D, 3 * d, 0, (int)batch, e, st))
+        return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
+      hipLaunchKernelGGL(cayley_update_kernel, dim3(ub, (unsigned)batch), dim3(256), 0, st, Mm, Rt, Zt,
+                         Us[(it + 1) & 1], D, delta, it, kCayleyMaxIters, kCayleyTol);
+      if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley update launch failed");
+    }
+  } else {
   // M = dR R^T
   {
     EpiStore<TF> e;
@@ -452,15 +492,16 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, delta, batch * kCayleyMaxIters, 0u);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "fill launch failed");
   hipLaunchKernelGGL(cayley_setup_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Mm, R,
-                     D, 0.5f * lr, Bm, Rt, Zt, U[0]);
+                     D, 0.5f * lr, Bm, Rt, Zt, U[0], (__bf16*)nullptr, (__bf16*)nullptr);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley set-up launch failed");
   // fixed point in transposed space: Zt <- Rt - U Bm^T, U <- Rt + Zt
   for (int it = 0; it < kCayleyMaxIters; ++it) {
     EpiCayleyIter<TF> e;
-    e.Rt = Rt; e.Zt = Zt; e.Unew = U[(it + 1) & 1]; e.delta = delta;
+    e.Rt = Rt; e.Zt = Zt; e.Unew = U[(it + 1) & 1]; e.Usplit = nullptr; e.delta = delta;
     e.d = D; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
     if (!launch_gemm<TF>(U[it & 1], d, dd, D, Bm, d, dd, D, d, 0, (int)batch, e, st))
       return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
+  }
   }
   hipLaunchKernelGGL(cayley_finish_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Zt, D,
                      R, static_cast<__bf16*>(R_lowp), delta, kCayleyMaxIters, kCayleyTol, info);

@@ -140,14 +140,43 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   }
 }
 
+// fp32 value -> bf16 head and bf16 tail (x ~ hi + lo to about 2^-17 relative).
+__device__ __forceinline__ void split_bf16(float x, __bf16& hi, __bf16& lo) {
+  hi = (__bf16)x;
+  lo = (__bf16)(x - (float)hi);
+}
+
+// Three-term bf16 emulation of an fp32 NT GEMM on the bf16 matrix cores:
+//   A B^T ~ A_hi B_hi^T + A_hi B_lo^T + A_lo B_hi^T
+// written as ONE bf16 GEMM with K tripled: the left operand is stored as [hi | hi | lo]
+// (3*cols wide), the right operand as [hi | lo | hi].  `right` selects the layout.
+// grid-stride over rows*cols elements; grid.z = batch.
+__global__ __launch_bounds__(256) void split3_kernel(const float* __restrict__ in, int rows, int cols,
+                                                     __bf16* __restrict__ out, int right) {
+  const int64_t total = (int64_t)rows * cols;
+  in += (int64_t)blockIdx.z * total;
+  out += (int64_t)blockIdx.z * total * 3;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / cols, c = i - r * cols;
+    __bf16 hi, lo;
+    split_bf16(in[i], hi, lo);
+    __bf16* o = out + r * 3 * cols + c;
+    o[0] = hi;
+    o[cols] = right ? lo : hi;
+    o[2 * (int64_t)cols] = right ? hi : lo;
+  }
+}
+
 // Cayley set-up: from M = dR R^T build  Bm = (lr/2)(M - M^T)  (exactly skew),
-// Rt = R^T, Zt0 = Rt, U0 = 2 Rt.  32 x 32 tiles; grid = (d/32, d/32, batch).
+// Rt = R^T, Zt0 = Rt, U0 = 2 Rt (Bm and U0 either as fp32 or as split bf16 operands).  32 x 32 tiles; grid = (d/32, d/32, batch).
 __global__ __launch_bounds__(256) void cayley_setup_kernel(const float* __restrict__ Mm,
                                                            const float* __restrict__ R, int d,
                                                            float half_lr, float* __restrict__ Bm,
                                                            float* __restrict__ Rt,
                                                            float* __restrict__ Zt,
-                                                           float* __restrict__ U0) {
+                                                           float* __restrict__ U0,
+                                                           __bf16* __restrict__ Bs,
+                                                           __bf16* __restrict__ Us) {
   __shared__ float tm[32][33];
   __shared__ float tr[32][33];
   const int64_t bo = (int64_t)blockIdx.z * d * d;
@@ -167,12 +196,68 @@ __global__ __launch_bounds__(256) void cayley_setup_kernel(const float* __restri
     const int64_t idx = bo + (int64_t)(i0 + rr) * d + j0 + tx;
     const float m_ij = Mm[idx];
     const float m_ji = tm[tx][rr];
-    Bm[idx] = half_lr * (m_ij - m_ji);
+    const float b = half_lr * (m_ij - m_ji);
     const float rt = tr[tx][rr];  // R[j0+tx][i0+rr] = Rt[i0+rr][j0+tx]
     Rt[idx] = rt;
     Zt[idx] = rt;
-    U0[idx] = 2.f * rt;
+    if (Bs) {  // split operands of the three-term bf16 GEMM: B as [hi|lo|hi], U as [hi|hi|lo]
+      const int64_t so = 3 * bo + (int64_t)(i0 + rr) * 3 * d + j0 + tx;
+      __bf16 hi, lo;
+      split_bf16(b, hi, lo);
+      Bs[so] = hi; Bs[so + d] = lo; Bs[so + 2 * d] = hi;
+      split_bf16(2.f * rt, hi, lo);
+      Us[so] = hi; Us[so + d] = hi; Us[so + 2 * d] = lo;
+    } else {
+      Bm[idx] = b;
+      U0[idx] = 2.f * rt;
+    }
   }
+}
+
+// One fixed-point update from the GEMM product C = U B^T (three-term bf16 path):
+//   Zt_new = Rt - C;  delta[it] = max |Zt_new - Zt|;  U_next = Rt + Zt_new as [hi|hi|lo].
+// Four consecutive elements per thread (16-byte loads); grid-stride; grid.y = batch.
+// Returns at once (handing the delta on) when an earlier iteration has converged.
+__global__ __launch_bounds__(256) void cayley_update_kernel(const float* __restrict__ C,
+                                                            const float* __restrict__ Rt,
+                                                            float* __restrict__ Zt,
+                                                            __bf16* __restrict__ Us, int d,
+                                                            unsigned* __restrict__ delta, int it,
+                                                            int max_iters, float tol) {
+  __shared__ unsigned sh[4];
+  unsigned* dl = delta + (int64_t)blockIdx.y * max_iters;
+  if (it > 0 && cayley_converged(dl, it - 1, tol)) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) dl[it] = dl[it - 1];
+    return;
+  }
+  const int64_t dd = (int64_t)d * d, bo = (int64_t)blockIdx.y * dd;
+  unsigned dmax = 0u;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < dd / 4; q += (int64_t)gridDim.x * 256) {
+    const int64_t i = q * 4;
+    const int64_t m = i / d, n = i - m * d;
+    const floatx4 c = *reinterpret_cast<const floatx4*>(C + bo + i);
+    const floatx4 rt = *reinterpret_cast<const floatx4*>(Rt + bo + i);
+    const floatx4 zo = *reinterpret_cast<const floatx4*>(Zt + bo + i);
+    floatx4 z;
+    __bf16 hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      z[e] = rt[e] - c[e];
+      dmax = umax(dmax, abs_bits(z[e] - zo[e]));
+      split_bf16(rt[e] + z[e], hi[e], lo[e]);
+    }
+    *reinterpret_cast<floatx4*>(Zt + bo + i) = z;
+    __bf16* o = Us + 3 * bo + m * 3 * d + n;
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    const bf16x4 vh = {hi[0], hi[1], hi[2], hi[3]}, vl = {lo[0], lo[1], lo[2], lo[3]};
+    *reinterpret_cast<bf16x4*>(o) = vh;
+    *reinterpret_cast<bf16x4*>(o + d) = vh;
+    *reinterpret_cast<bf16x4*>(o + 2 * (int64_t)d) = vl;
+  }
+  dmax = wave_umax(dmax);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = dmax;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(&dl[it], umax(umax(sh[0], sh[1]), umax(sh[2], sh[3])));
 }
 
 // Cayley wrap-up: R = Zt^T (and its bf16 copy), info = iterations used or -1.
@@ -203,7 +288,7 @@ __global__ __launch_bounds__(256) void cayley_finish_kernel(const float* __restr
   if (info && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
     int used = -1;
     for (int k = 0; k < max_iters; ++k) {
-      if (__uint_as_float(delta[(int64_t)blockIdx.z * max_iters + k]) <= tol) { used = k + 1; break; }
+      if (cayley_converged(delta + (int64_t)blockIdx.z * max_iters, k, tol)) { used = k + 1; break; }
     }
     info[blockIdx.z] = used;
   }

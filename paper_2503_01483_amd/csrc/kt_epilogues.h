@@ -141,20 +141,34 @@ __device__ __forceinline__ unsigned wave_umax(unsigned v) {
 // delta[it] = max |Zt_new - Zt_old| (bit pattern of a non-negative float, max is
 // order independent so the result is deterministic).  The launch for iteration `it`
 // returns at once when iteration it-1 already met the tolerance.
+// Iteration k counts as converged when its delta is below the tolerance, or when it is
+// small (within 64 tolerances) and has stopped shrinking (>= 0.9 of the previous one):
+// the iterate then sits on the rounding floor of the arithmetic, which for the three-term
+// bf16 products lies at a few 1e-7 and would never pass a fixed fp32-sized tolerance.
+__device__ __forceinline__ bool cayley_converged(const unsigned* dl, int k, float tol) {
+  const float d1 = __uint_as_float(dl[k]);
+  if (d1 <= tol) return true;
+  if (k == 0 || !(d1 <= 64.f * tol)) return false;
+  return d1 >= 0.9f * __uint_as_float(dl[k - 1]);
+}
+
+// Unew is written as fp32, or (Usplit != null) as the [hi | hi | lo] bf16 operand of the
+// three-term bf16 GEMM that runs the next iteration.
 template <class TL>
 struct EpiCayleyIter {
   const float* Rt;
   float* Zt;
   float* Unew;
+  __bf16* Usplit;
   unsigned* delta;  // [batch][max_iters]
   int d, it, max_iters;
   float tol;
   __device__ __forceinline__ bool skip(int batch) const {
     if (it == 0) return false;
-    const unsigned bits = delta[(int64_t)batch * max_iters + it - 1];
-    if (!(__uint_as_float(bits) <= tol)) return false;
+    const unsigned* dl = delta + (int64_t)batch * max_iters;
+    if (!cayley_converged(dl, it - 1, tol)) return false;
     // converged earlier: hand the small delta on so that later launches return too
-    if (blockIdx.x == 0 && threadIdx.x == 0) delta[(int64_t)batch * max_iters + it] = bits;
+    if (blockIdx.x == 0 && threadIdx.x == 0) delta[(int64_t)batch * max_iters + it] = dl[it - 1];
     return true;
   }
   __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
@@ -176,12 +190,34 @@ struct EpiCayleyIter {
             const float z = rt - acc[mb][nb][r];
             dmax = umax(dmax, abs_bits(z - Zt[idx]));
             Zt[idx] = z;
-            Unew[idx] = rt + z;
+            const float u = rt + z;
+            if (Usplit) {
+              const int64_t so = 3 * bo + (int64_t)m * 3 * d + n;
+              const __bf16 hi = (__bf16)u;
+              const __bf16 lo = (__bf16)(u - (float)hi);
+              Usplit[so] = hi;
+              Usplit[so + d] = hi;
+              Usplit[so + 2 * d] = lo;
+            } else {
+              Unew[idx] = u;
+            }
           }
         }
       }
     dmax = wave_umax(dmax);
     if (f.lane == 0) atomicMax(&delta[(int64_t)batch * max_iters + it], dmax);
+  }
+};
+
+// Plain fp32 store of one Cayley iteration's product (the update runs as a separate
+// elementwise kernel); returns at once when an earlier iteration has converged.
+template <class TL>
+struct EpiCayleyProduct : EpiStore<TL> {
+  const unsigned* delta;  // [batch][max_iters]
+  int it, max_iters;
+  float tol;
+  __device__ __forceinline__ bool skip(int batch) const {
+    return it > 0 && cayley_converged(delta + (int64_t)batch * max_iters, it - 1, tol);
   }
 };
 

@@ -200,7 +200,11 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
 
   auto gload = [&](auto i_c, int slab) __attribute__((always_inline)) {
     constexpr int i = decltype(i_c)::value;
+#ifdef KT_EXP_NOADV
+    const char* base = (i < A_LD ? Ab : Bb) + (int64_t)(slab & 1) * kRowBytes;
+#else
     const char* base = (i < A_LD ? Ab : Bb) + (int64_t)slab * kRowBytes;
+#endif
     rg[i] = *reinterpret_cast<const intx4*>(base + og[i]);
   };
   auto lstore = [&](auto i_c, auto stage_c) __attribute__((always_inline)) {

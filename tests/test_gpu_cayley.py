@@ -38,7 +38,22 @@ def test_against_oracle(d, batch, lr, gscale):
         assert float((RtR - torch.eye(d, dtype=torch.float64)).abs().max()) < 1e-6
         # the library's own figure is an fp32 GEMM: true value plus a few ulp of 1
         assert oe[b] < 1e-6 and abs(oe[b] - float((RtR - torch.eye(d, dtype=torch.float64)).abs().max())) < 6e-7
-        assert 1 <= info[b] <= 48
+        assert 1 <= info[b] <= 32
+    assert torch.equal(lowp, Rn.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("d,lr,gscale", [(1024, 1e-2, 1.0), (1024, 0.2, 2.0), (2048, 1e-2, 1.0)])
+def test_large_d_three_term_bf16_path(d, lr, gscale):
+    # d >= 1024 runs its GEMMs as three-term bf16 products; same bars as the fp32 path
+    g = torch.Generator().manual_seed(d)
+    R = ktgen.random_orthogonal(d, seed=3).unsqueeze(0)
+    G = torch.randn((1, d, d), generator=g) * gscale / np.sqrt(d)
+    Rn, lowp, oe, info = _run(R, G, lr)
+    ref = oracle.cayley_step(ktgen.to_f64(R[0]), ktgen.to_f64(G[0]), lr)
+    assert rel_fro(Rn[0].numpy().astype(np.float64) - ktgen.to_f64(R[0]), ref - ktgen.to_f64(R[0])) <= 1e-4
+    RtR = Rn[0].double().T @ Rn[0].double()
+    assert float((RtR - torch.eye(d, dtype=torch.float64)).abs().max()) < 1e-6
+    assert oe[0] < 1e-6 and 1 <= info[0] <= 32
     assert torch.equal(lowp, Rn.to(torch.bfloat16))
 
 
