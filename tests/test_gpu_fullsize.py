@@ -1,0 +1,77 @@
+"""GPU parity at the benchmark's full size (C3: d = 4096, n = 131072, bf16), in the launch
+configuration bench.py times.  The oracle cannot do the whole problem, so: per-row kurtosis on
+sampled rows and loss/gradient on a 1024-row chunk are compared with the oracle directly, and
+the full result is tied to them by properties that hold at any size (invariants of the gradient,
+the loss as the mean of the row values, additivity over row chunks)."""
+import numpy as np
+import pytest
+import torch
+
+import ktgen
+import oracle
+import paper_2503_01483_amd as kt
+from parity_util import rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c3_full_size():
+    X, R, cfg = ktgen.make_problem("C3", seed=0, device="cuda")
+    b, n, d = X.shape
+    assert (n, d) == (131072, 4096)
+    ws = kt.Workspace()
+    rk = torch.empty((1, n), device="cuda")
+    dR = torch.empty((1, d, d), device="cuda")
+    loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    rk_h = rk[0].cpu().numpy().astype(np.float64)
+    dR_h = dR[0].cpu().numpy().astype(np.float64)
+    Rb = ktgen.to_f64(ktgen.bf16_round(R[0]))
+
+    # loss is the mean of the per-row values
+    assert abs(loss.item() - rk_h.mean()) <= 1e-5 * rk_h.mean()
+    # sampled rows against the oracle, one by one
+    rows = np.random.default_rng(0).choice(n, size=96, replace=False)
+    o = oracle.loss_grad(ktgen.to_f64(X[0, torch.as_tensor(rows, device="cuda")]), Rb, want_dR=False)
+    assert np.max(np.abs(rk_h[rows] - o["row_kurt"]) / o["row_kurt"]) <= 2e-2
+    # invariants of the gradient (shift / scale invariance of kurtosis), no oracle needed
+    nrm = np.linalg.norm(dR_h)
+    assert np.linalg.norm(dR_h.sum(1)) <= 1e-3 * nrm * np.sqrt(d)
+    assert abs((dR_h * Rb).sum()) <= 1e-3 * nrm * np.linalg.norm(Rb)
+
+    # a chunk the oracle can do, at the real d
+    m = 1024
+    l2 = torch.empty(1, device="cuda")
+    d2 = torch.empty((1, d, d), device="cuda")
+    kt.kt_kurtosis_loss_grad(X[:, :m], R, loss=l2, dR=d2, workspace=ws)
+    torch.cuda.synchronize()
+    oc = oracle.loss_grad(ktgen.to_f64(X[0, :m]), Rb)
+    assert abs(l2.item() - oc["loss"]) <= 2e-2 * oc["loss"]
+    assert rel_fro(d2[0].cpu().numpy(), oc["dR"]) <= 2e-2
+
+    # additivity over four row chunks ties the full gradient to chunk results
+    acc = np.zeros((d, d))
+    q = n // 4
+    for c in range(4):
+        kt.kt_kurtosis_loss_grad(X[:, c * q:(c + 1) * q], R, loss=l2, dR=d2, workspace=ws)
+        torch.cuda.synchronize()
+        acc += q * d2[0].cpu().numpy().astype(np.float64)
+    assert rel_fro(n * dR_h, acc) <= 5e-3
+
+
+def test_c3_full_size_step_is_orthogonal_and_descends():
+    X, R, cfg = ktgen.make_problem("C3", seed=0, device="cuda", n=32768)
+    d = cfg["d"]
+    ws = kt.Workspace()
+    dR = torch.empty((1, d, d), device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    oe = torch.zeros(1, device="cuda")
+    Rw = R.clone()
+    l0 = kt.kt_kurtosis_loss_grad(X, Rw, dR=dR, workspace=ws).item()
+    kt.kt_cayley_step(Rw, dR, 1e-2, ortho_err=oe, info=info, workspace=ws)
+    l1 = kt.kt_kurtosis_loss_grad(X, Rw, workspace=ws).item()
+    torch.cuda.synchronize()
+    assert 1 <= info.item() <= 32 and oe.item() < 1e-6
+    RtR = Rw[0].double().T @ Rw[0].double()
+    assert float((RtR - torch.eye(d, dtype=torch.float64, device="cuda")).abs().max()) < 1e-6
+    assert l1 < l0
