@@ -295,9 +295,15 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   // token-minor copy of X for the last GEMM (zero padded to ldt tokens)
   {
     ProfScope prof(3, st);
-    dim3 grid((unsigned)(p.ldt / 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
-    hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.ldt,
-                       d * p.ldt, (int)n, (int)p.ldt, (int)d);
+    if (sizeof(T) == 2) {
+      dim3 grid((unsigned)ceil_div(p.ldt, 128), (unsigned)(d / 64), (unsigned)batch);
+      hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const uint16_t*>(Xp),
+                         ldx, n * ldx, reinterpret_cast<uint16_t*>(XT), p.ldt, d * p.ldt, (int)n, (int)p.ldt);
+    } else {
+      dim3 grid((unsigned)(p.ldt / 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
+      hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.ldt,
+                         d * p.ldt, (int)n, (int)p.ldt, (int)d);
+    }
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "X transpose launch failed");
   }
   // a3: recompute Y, write dL/dY token-minor

@@ -37,6 +37,49 @@ __global__ __launch_bounds__(256) void transpose_kernel(const Tin* __restrict__ 
   }
 }
 
+// Same operation for 2-byte elements with 16-byte global accesses on both sides:
+// tile = 128 rows x 64 cols; each thread moves four 16-byte chunks in and four out.
+// Needs cols % 64 == 0, rows_pad % 8 == 0, ldi % 8 == 0, ldo % 8 == 0.
+// grid = (ceil(rows_pad/128), cols/64, batch)
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, int64_t ldi,
+                                                          int64_t in_batch_stride,
+                                                          uint16_t* __restrict__ out, int64_t ldo,
+                                                          int64_t out_batch_stride, int rows,
+                                                          int rows_pad) {
+  constexpr int PITCH = 33;  // dwords per tile row (64 elements + 1 dword of skew)
+  __shared__ uint32_t tile[128 * PITCH];
+  const int r0 = blockIdx.x * 128, c0 = blockIdx.y * 64;
+  in += (int64_t)blockIdx.z * in_batch_stride;
+  out += (int64_t)blockIdx.z * out_batch_stride;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + i * 256;
+    const int row = c >> 3, col8 = c & 7;
+    intx4 v = {0, 0, 0, 0};
+    if (r0 + row < rows) v = *reinterpret_cast<const intx4*>(in + (int64_t)(r0 + row) * ldi + c0 + col8 * 8);
+    uint32_t* t = tile + row * PITCH + col8 * 4;
+    t[0] = (uint32_t)v[0]; t[1] = (uint32_t)v[1]; t[2] = (uint32_t)v[2]; t[3] = (uint32_t)v[3];
+  }
+  __syncthreads();
+  const uint16_t* t16 = reinterpret_cast<const uint16_t*>(tile);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + i * 256;
+    const int f = c >> 4, t8 = c & 15;
+    if (r0 + t8 * 8 < rows_pad) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t lo = t16[(t8 * 8 + 2 * e) * (2 * PITCH) + f];
+        const uint32_t hi = t16[(t8 * 8 + 2 * e + 1) * (2 * PITCH) + f];
+        w[e] = lo | (hi << 16);
+      }
+      intx4 v = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+      *reinterpret_cast<intx4*>(out + (int64_t)(c0 + f) * ldo + r0 + t8 * 8) = v;
+    }
+  }
+}
+
 // Row-major copy with dtype conversion: out[r*ldo + c] = in[r*ldi + c].
 template <typename Tin, typename Tout>
 __global__ __launch_bounds__(256) void convert_kernel(const Tin* __restrict__ in, int64_t ldi,
