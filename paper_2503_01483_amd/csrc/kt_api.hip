@@ -125,7 +125,7 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   LossGradPlan p;
   p.fp32 = (xdt == KT_F32);
   p.esz = p.fp32 ? 4 : 2;
-  p.ldt = round_up(n, 64);
+  p.ldt = round_up(n, 128);
   int64_t slabs;
   if (p.fp32) {
     p.P = (int)ceil_div(d, TF::BM) * TF::WGM;
@@ -250,10 +250,10 @@ static bool prep_rt(const void* R, int64_t ldr, kt_dtype rdt, Tout* RT, int64_t 
   dim3 grid((unsigned)ceil_div(d, 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
   if (rdt == KT_F32)
     hipLaunchKernelGGL((transpose_kernel<float, Tout>), grid, dim3(256), 0, st,
-                       static_cast<const float*>(R), ldr, d * ldr, RT, d, d * d, (int)d, (int)d, (int)d);
+                       static_cast<const float*>(R), ldr, d * ldr, RT, d, d * d, (int)d, (int)d, (int)d, 0);
   else
     hipLaunchKernelGGL((transpose_kernel<bf16, Tout>), grid, dim3(256), 0, st,
-                       static_cast<const bf16*>(R), ldr, d * ldr, RT, d, d * d, (int)d, (int)d, (int)d);
+                       static_cast<const bf16*>(R), ldr, d * ldr, RT, d, d * d, (int)d, (int)d, (int)d, 0);
   return launch_ok();
 }
 
@@ -302,7 +302,7 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
     } else {
       dim3 grid((unsigned)(p.ldt / 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
       hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.ldt,
-                         d * p.ldt, (int)n, (int)p.ldt, (int)d);
+                         d * p.ldt, (int)n, (int)p.ldt, (int)d, 1);
     }
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "X transpose launch failed");
   }

@@ -8,15 +8,17 @@ namespace kt {
 template <typename Tin>
 __device__ __forceinline__ float to_float(Tin v) { return (float)v; }
 
-// out[c*ldo + r] = in[r*ldi + c] for r < rows, c < cols; columns r in [rows, rows_pad)
-// of `out` are zero-filled.  64 x 64 tiles through LDS, 256 threads.
+// out[c*ldo + r'] = in[r*ldi + c] for r < rows, c < cols; columns r in [rows, rows_pad)
+// of `out` are zero-filled.  r' = r, or token_position(r) when `permute` is set (the
+// token order of the X^T G operands; rows_pad must then be a multiple of 128).
+// 64 x 64 tiles through LDS, 256 threads.
 // grid = (ceil(rows_pad/64), ceil(cols/64), batch)
 template <typename Tin, typename Tout>
 __global__ __launch_bounds__(256) void transpose_kernel(const Tin* __restrict__ in, int64_t ldi,
                                                         int64_t in_batch_stride,
                                                         Tout* __restrict__ out, int64_t ldo,
                                                         int64_t out_batch_stride, int rows,
-                                                        int rows_pad, int cols) {
+                                                        int rows_pad, int cols, int permute) {
   __shared__ float tile[64][65];
   const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -33,13 +35,15 @@ __global__ __launch_bounds__(256) void transpose_kernel(const Tin* __restrict__ 
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int c = c0 + ty + 4 * i, r = r0 + tx;
-    if (c < cols && r < rows_pad) out[(int64_t)c * ldo + r] = from_float<Tout>(tile[tx][ty + 4 * i]);
+    if (c < cols && r < rows_pad)
+      out[(int64_t)c * ldo + (permute ? token_position(r) : (int64_t)r)] = from_float<Tout>(tile[tx][ty + 4 * i]);
   }
 }
 
-// Same operation for 2-byte elements with 16-byte global accesses on both sides:
-// tile = 128 rows x 64 cols; each thread moves four 16-byte chunks in and four out.
-// Needs cols % 64 == 0, rows_pad % 8 == 0, ldi % 8 == 0, ldo % 8 == 0.
+// The token-minor, token-permuted copy of X for 2-byte elements, with 16-byte global
+// accesses on both sides: out[c*ldo + token_position(r)] = in[r*ldi + c].
+// tile = 128 rows (one token group) x 64 cols; each thread moves four 16-byte chunks in
+// and four out.  Needs cols % 64 == 0, rows_pad % 128 == 0, ldi % 8 == 0, ldo % 8 == 0.
 // grid = (ceil(rows_pad/128), cols/64, batch)
 __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, int64_t ldi,
                                                           int64_t in_batch_stride,
@@ -70,8 +74,10 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
       uint32_t w[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const uint32_t lo = t16[(t8 * 8 + 2 * e) * (2 * PITCH) + f];
-        const uint32_t hi = t16[(t8 * 8 + 2 * e + 1) * (2 * PITCH) + f];
+        // output position p of the group holds token (p & 3) * 32 + (p >> 2)
+        const int p = t8 * 8 + 2 * e;
+        const uint32_t lo = t16[(((p & 3) << 5) + (p >> 2)) * (2 * PITCH) + f];
+        const uint32_t hi = t16[((((p + 1) & 3) << 5) + ((p + 1) >> 2)) * (2 * PITCH) + f];
         w[e] = lo | (hi << 16);
       }
       intx4 v = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};

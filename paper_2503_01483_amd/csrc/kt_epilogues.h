@@ -63,8 +63,20 @@ struct EpiMoments : EpiBase {
 
 // ---- backward pass: recomputed y -> dL/dy, stored token-minor ---------------------
 // coef[token] = {alpha, mu, beta, m3};  g = alpha * (c (c^2 - beta) - m3), c = y - mu.
-// GT[(batch*d + feature)*ldt + token]; tokens in [n_tokens, ldt) are written as zero
-// so the padded K range of the following X^T G GEMM contributes nothing.
+//
+// Layout of GT (and of the token-minor copy of X that meets it in dR = X^T G): rows are
+// features, and inside every group of 128 tokens the tokens are PERMUTED,
+//     position(t) = (t & 31) * 4 + ((t & 127) >> 5),
+// because the contraction over tokens does not care in which order the tokens come as
+// long as both operands agree.  In the accumulator layout a lane owns tokens
+// t, t+32, t+64, t+96 of a group, so with this order its values for one feature are
+// ADJACENT in memory: one 8-byte store per feature instead of four 2-byte ones, and 32
+// lanes cover 256 contiguous bytes.  Tokens in [n_tokens, ldt) are written as zero so the
+// padded K range contributes nothing; ldt is a multiple of 128.
+__host__ __device__ __forceinline__ int64_t token_position(int64_t t) {
+  return (t & ~(int64_t)127) + ((t & 31) << 2) + ((t & 127) >> 5);
+}
+
 template <class TL>
 struct EpiGrad : EpiBase {
   using T = typename TL::T;
@@ -72,28 +84,39 @@ struct EpiGrad : EpiBase {
   T* GT;
   int64_t ldt;
   int n_tokens, d;
+  static_assert(TL::BN % 128 == 0 && (TL::WTN == 128 || TL::WTN == 64), "token groups are 128 wide");
   __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
                                              int, int, int m0, int n0) const {
+    typedef T vecT __attribute__((ext_vector_type(TL::NB)));
     const Frag<TL> f;
+    const int wave_tok0 = n0 + f.wn * TL::WTN;            // first token of this wave
+    const int group0 = wave_tok0 & ~127;                   // its 128-token group
+    if (group0 >= ldt) return;
+    // lane's tokens: wave_tok0 + nb*32 + (lane & 31); positions are consecutive in nb
+    const int64_t pos0 = group0 + ((f.lane & 31) << 2) + ((wave_tok0 & 127) >> 5);
+    float alpha[TL::NB], mu[TL::NB], beta[TL::NB], m3[TL::NB];
 #pragma unroll
     for (int nb = 0; nb < TL::NB; ++nb) {
       const int token = n0 + f.n_of(nb);
-      if (token >= ldt) continue;
-      const bool valid = token < n_tokens;
-      floatx4 c4 = {0.f, 0.f, 0.f, 0.f};
-      if (valid) c4 = coef[(int64_t)batch * n_tokens + token];
-      const float alpha = c4[0], mu = c4[1], beta = c4[2], m3 = c4[3];
+      floatx4 c4 = {0.f, 0.f, 0.f, 0.f};  // alpha = 0 zeroes the padding tokens
+      if (token < n_tokens) c4 = coef[(int64_t)batch * n_tokens + token];
+      alpha[nb] = c4[0]; mu[nb] = c4[1]; beta[nb] = c4[2]; m3[nb] = c4[3];
+    }
 #pragma unroll
-      for (int mb = 0; mb < TL::MB; ++mb) {
-        if (m0 + f.m_block(mb) < d) {
+    for (int mb = 0; mb < TL::MB; ++mb) {
+      if (m0 + f.m_block(mb) < d) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float c = acc[mb][nb][r] - mu;
-            float g = alpha * fmaf(c, fmaf(c, c, -beta), -m3);
-            if (!valid) g = 0.f;
-            const int feat = m0 + f.m_of(mb, r);
-            GT[((int64_t)batch * d + feat) * ldt + token] = from_float<T>(g);
+        for (int r = 0; r < 16; ++r) {
+          vecT v;
+#pragma unroll
+          for (int nb = 0; nb < TL::NB; ++nb) {
+            const float c = acc[mb][nb][r] - mu[nb];
+            float g = alpha[nb] * fmaf(c, fmaf(c, c, -beta[nb]), -m3[nb]);
+            if (alpha[nb] == 0.f) g = 0.f;
+            v[nb] = from_float<T>(g);
           }
+          const int feat = m0 + f.m_of(mb, r);
+          *reinterpret_cast<vecT*>(GT + ((int64_t)batch * d + feat) * ldt + pos0) = v;
         }
       }
     }
