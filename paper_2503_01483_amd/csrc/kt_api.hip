@@ -90,10 +90,11 @@ static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const vo
   return launch_ok();
 }
 
-// K slabs per split so that `tiles` output tiles give about one workgroup per CU,
-// with at least 8 slabs of work in each split.
-static int choose_slabs_per_split(int64_t tiles, int64_t slabs_total) {
-  int64_t s = ceil_div(kNumCUs, tiles);
+// K slabs per split so that `tiles` output tiles give about `target_wgs` workgroups
+// (one per CU for 256 x 256 tiles, several for the small tiles that share a CU), with at
+// least 8 slabs of work in each split.
+static int choose_slabs_per_split(int64_t tiles, int64_t slabs_total, int64_t target_wgs) {
+  int64_t s = ceil_div(target_wgs, tiles);
   const int64_t cap = slabs_total / 8 > 0 ? slabs_total / 8 : 1;
   if (s > cap) s = cap;
   if (s < 1) s = 1;
@@ -140,7 +141,9 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
     p.tiles_dd = (int)(ceil_div(d, 128) * ceil_div(d, 128));
     slabs = p.ldt / TB_128::BK;
   }
-  p.slabs_per_split = choose_slabs_per_split((int64_t)p.tiles_dd * batch, slabs);
+  const bool big_tiles = !p.fp32 && d % 256 == 0;
+  p.slabs_per_split = choose_slabs_per_split((int64_t)p.tiles_dd * batch, slabs,
+                                             big_tiles ? kNumCUs : 4 * kNumCUs);
   p.split_k = (int)ceil_div(slabs, p.slabs_per_split);
   p.loss_blocks = (int)ceil_div(n, 256);
   Carver c;
@@ -222,8 +225,9 @@ static kt_status check_xr(const void* X, int64_t ldx, const void* R, int64_t ldr
   if (xdt == KT_F32 && rdt != KT_F32)
     return fail(KT_ERR_BAD_DTYPE, "the fp32 path needs an fp32 R");
   if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
-  if (d > 32768 || n > (int64_t)1 << 30 || batch > 65535)
-    return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 32768, n <= 2^30, batch <= 65535)");
+  // n is bounded so that 255 rows of a token-minor operand stay inside 32-bit byte offsets
+  if (d > 32768 || n > (int64_t)1 << 22 || batch > 65535)
+    return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 32768, n <= 2^22, batch <= 65535)");
   const int64_t align = xdt == KT_F32 ? 4 : 8;
   if (ldx < d || ldx % align != 0)
     return fail(KT_ERR_BAD_SHAPE, "ldx = %lld must be >= d and a multiple of %lld", (long long)ldx,
@@ -465,23 +469,26 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
     hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, dR, D, D, Us[0], 0);
     hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, R, D, D, Us[1], 1);
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "split launch failed");
-    {
-      EpiStore<TB_BIG> e;
-      e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
-      if (!launch_gemm<TB_BIG>(Us[0], 3 * d, sd, D, Us[1], 3 * d, sd, D, 3 * d, 0, (int)batch, e, st))
-        return fail(KT_ERR_DEVICE, "dR R^T GEMM launch failed");
-    }
+    // below d = 4096 a 256 x 256 tiling leaves most CUs without a tile: use 128 x 128 there
+    const bool big = (d / 256) * (d / 256) * batch >= kNumCUs;
+    auto product = [&](const __bf16* A3, const __bf16* B3, int it) -> bool {
+      auto go = [&](auto tile_tag) -> bool {
+        using TL = decltype(tile_tag);
+        EpiCayleyProduct<TL> e;
+        e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
+        e.delta = delta; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
+        return launch_gemm<TL>(A3, 3 * d, sd, D, B3, 3 * d, sd, D, 3 * d, 0, (int)batch, e, st);
+      };
+      return big ? go(TB_BIG{}) : go(TB_128{});
+    };
+    if (!product(Us[0], Us[1], 0)) return fail(KT_ERR_DEVICE, "dR R^T GEMM launch failed");
     hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, delta, batch * kCayleyMaxIters, 0u);
     hipLaunchKernelGGL(cayley_setup_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Mm, R,
                        D, 0.5f * lr, (float*)nullptr, Rt, Zt, (float*)nullptr, Bs, Us[0]);
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley set-up launch failed");
     const unsigned ub = (unsigned)(ceil_div(dd / 4, 256) < 2048 ? ceil_div(dd / 4, 256) : 2048);
     for (int it = 0; it < kCayleyMaxIters; ++it) {
-      EpiCayleyProduct<TB_BIG> e;
-      e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
-      e.delta = delta; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
-      if (!launch_gemm<TB_BIG>(Us[it & 1], 3 * d, sd, D, Bs, 3 * d, sd, D, 3 * d, 0, (int)batch, e, st))
-        return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
+      if (!product(Us[it & 1], Bs, it)) return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
       hipLaunchKernelGGL(cayley_update_kernel, dim3(ub, (unsigned)batch), dim3(256), 0, st, Mm, Rt, Zt,
                          Us[(it + 1) & 1], D, delta, it, kCayleyMaxIters, kCayleyTol);
       if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley update launch failed");
