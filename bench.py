@@ -23,6 +23,10 @@ PEAK_F32_TFLOPS = 157.3     # MI355X fp32 matrix
 KERNEL_NAMES = {0: "gemm_nt_kernel<bf16 256x256, EpiMoments> (forward + row moments)",
                 1: "gemm_nt_kernel<bf16 256x256, EpiGrad> (recompute + dL/dY)",
                 2: "gemm_nt_kernel<bf16 256x256, EpiStore> (dR = X^T G)"}
+# Fabric-side bytes per launch (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, calibrated on a 1 GiB
+# device copy; see profiles/c3_gemm_counters.md).  Counters need a profiler run of their own, so the
+# figures measured for the default workload are carried here as constants; other workloads report null.
+MEASURED_TRAFFIC_BYTES = {"C3": {0: (6.00 + 0.0625) * 2**30, 1: (6.01 + 1.0) * 2**30, 2: (11.8 + 0.0625) * 2**30}}
 CPU_SAMPLE_ROWS = {"C1": 2048, "C2": 32768, "C3": 16384, "C4": 131072, "C5": 4096}
 
 
@@ -36,6 +40,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="after timing, copy X once with a plain device copy (a kernel of known traffic, "
+                         "2 x bytes(X), against which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (token rows would shard over "
@@ -84,6 +91,12 @@ def main():
     prof = {k: kt.kt_profile_read(k) for k in range(5)}
     kt.kt_profile_enable(0)
 
+    if args.pmc_calibration:
+        Xc = torch.empty_like(X)
+        Xc.copy_(X)
+        torch.cuda.synchronize()
+        del Xc
+
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = batch * n * args.steps / elapsed
     flops_launch = 2.0 * batch * n * d * d           # one GEMM launch: 2 n d^2 per problem
@@ -97,7 +110,8 @@ def main():
     roofline = {"bound": "mfma", "kernel": KERNEL_NAMES[dom] if bf16 else "gemm_nt_kernel<f32 128x128>",
                 "achieved": round(kern[dom]["tflops"], 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(kern[dom]["tflops"] / peak, 4), "avg_launch_ms": round(kern[dom]["avg_ms"], 4),
-                "flops_per_launch": flops_launch, "traffic": None}
+                "flops_per_launch": flops_launch,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dom) if args.n is None else None}
     breakdown = {"fwd_moments_ms": round(kern[0]["avg_ms"], 4), "bwd_recompute_ms": round(kern[1]["avg_ms"], 4),
                  "grad_xtg_ms": round(kern[2]["avg_ms"], 4),
                  "x_transpose_ms": round(prof[3][0] / max(prof[3][1], 1), 4),
