@@ -60,13 +60,18 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
 constexpr int kNumCUs = 256;
+// Token-minor operands (X^T, G^T) are stored in blocks of this many tokens: within a block a
+// feature row is contiguous, blocks follow each other feature-row-set by feature-row-set, so
+// the 256 rows a tile streams together span 2 MiB per block instead of one page per row.
+constexpr int64_t kTokenBlock = 4096;
 constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
 
 template <class TL, class Epi>
 static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const void* B, int64_t ldb,
                         int64_t bsb, int N, int64_t K, int slabs_per_split, int batch,
-                        const Epi& epi, hipStream_t stream) {
+                        const Epi& epi, hipStream_t stream, int64_t k_block = 0,
+                        int64_t block_stride_a = 0, int64_t block_stride_b = 0) {
   static bool attr_done = false;
   auto kern = gemm_nt_kernel<TL, Epi>;
   if (!attr_done) {
@@ -86,6 +91,11 @@ static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const vo
   g.split_k = (int)ceil_div(g.slabs_total, g.slabs_per_split);  // every split non-empty
   g.tiles_total = g.tiles_m * g.tiles_n * g.split_k;
   g.grid_padded = (int)round_up(g.tiles_total, 8);
+  // K blocking: rows hold K in blocks of k_block elements, block b of a row starts
+  // block_stride elements after block b-1 (k_block = 0: ordinary contiguous rows)
+  g.slabs_per_block = k_block > 0 ? (int)(k_block / TL::BK) : (g.slabs_total > 0 ? g.slabs_total : 1);
+  g.block_bytes_a = block_stride_a * (int64_t)sizeof(typename TL::T);
+  g.block_bytes_b = block_stride_b * (int64_t)sizeof(typename TL::T);
   hipLaunchKernelGGL(kern, dim3(g.grid_padded, batch), dim3(TL::NT), TL::LDS_BYTES, stream, g, epi);
   return launch_ok();
 }
@@ -114,7 +124,9 @@ struct Carver {
 struct LossGradPlan {
   bool fp32;
   size_t esz;
-  int64_t ldt;     // padded token count of the token-minor copies
+  int64_t ldt;     // padded token count of the token-minor copies (multiple of 128)
+  int64_t tb;      // tokens per block of the token-minor copies (row length inside a block)
+  int64_t nblk;    // blocks per feature row
   int P;           // moment partials per token
   int tiles_dd;    // tiles of the d x d output GEMM
   int slabs_per_split, split_k;
@@ -127,6 +139,8 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   p.fp32 = (xdt == KT_F32);
   p.esz = p.fp32 ? 4 : 2;
   p.ldt = round_up(n, 128);
+  p.tb = p.ldt < kTokenBlock ? p.ldt : kTokenBlock;
+  p.nblk = ceil_div(p.ldt, p.tb);
   int64_t slabs;
   if (p.fp32) {
     p.P = (int)ceil_div(d, TF::BM) * TF::WGM;
@@ -151,8 +165,8 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   p.o_part = c.take((size_t)batch * p.P * n * 16);
   p.o_coef = c.take((size_t)batch * n * 16);
   p.o_losspart = c.take((size_t)batch * p.loss_blocks * 8);
-  p.o_xt = c.take((size_t)batch * d * p.ldt * p.esz);
-  p.o_gt = c.take((size_t)batch * d * p.ldt * p.esz);
+  p.o_xt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
+  p.o_gt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
   p.o_splitk = c.take(p.split_k > 1 ? (size_t)p.split_k * batch * d * d * 4 : 0);
   p.total = c.off;
   return p;
@@ -302,11 +316,12 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
     if (sizeof(T) == 2) {
       dim3 grid((unsigned)ceil_div(p.ldt, 128), (unsigned)(d / 64), (unsigned)batch);
       hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, st, reinterpret_cast<const uint16_t*>(Xp),
-                         ldx, n * ldx, reinterpret_cast<uint16_t*>(XT), p.ldt, d * p.ldt, (int)n, (int)p.ldt);
+                         ldx, n * ldx, reinterpret_cast<uint16_t*>(XT), p.tb, d * p.nblk * p.tb, (int)n,
+                         (int)p.ldt, (int)d);
     } else {
       dim3 grid((unsigned)(p.ldt / 64), (unsigned)ceil_div(d, 64), (unsigned)batch);
-      hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.ldt,
-                         d * p.ldt, (int)n, (int)p.ldt, (int)d, 1);
+      hipLaunchKernelGGL((transpose_kernel<T, T>), grid, dim3(256), 0, st, Xp, ldx, n * ldx, XT, p.tb,
+                         d * p.nblk * p.tb, (int)n, (int)p.ldt, (int)d, 1);
     }
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "X transpose launch failed");
   }
@@ -314,7 +329,8 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   {
     ProfScope prof(1, st);
     EpiGrad<TFWD> e;
-    e.coef = coef; e.GT = GT; e.ldt = p.ldt; e.n_tokens = (int)n; e.d = (int)d;
+    e.coef = coef; e.GT = GT; e.ldt = p.ldt; e.tb = p.tb; e.batch_stride = d * p.nblk * p.tb;
+    e.n_tokens = (int)n; e.d = (int)d;
     if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
       return fail(KT_ERR_DEVICE, "backward recompute GEMM launch failed");
   }
@@ -328,8 +344,8 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
     } else {
       e.C = dR; e.batch_stride = d * d; e.split_stride = 0;
     }
-    if (!launch_gemm<TDD>(XT, p.ldt, d * p.ldt, (int)d, GT, p.ldt, d * p.ldt, (int)d, p.ldt,
-                          p.slabs_per_split, (int)batch, e, st))
+    if (!launch_gemm<TDD>(XT, p.tb, d * p.nblk * p.tb, (int)d, GT, p.tb, d * p.nblk * p.tb, (int)d, p.ldt,
+                          p.slabs_per_split, (int)batch, e, st, p.tb, d * p.tb, d * p.tb))
       return fail(KT_ERR_DEVICE, "gradient GEMM launch failed");
     if (p.split_k > 1) {
       const int64_t count = batch * d * d;

@@ -9,8 +9,9 @@ template <typename Tin>
 __device__ __forceinline__ float to_float(Tin v) { return (float)v; }
 
 // out[c*ldo + r'] = in[r*ldi + c] for r < rows, c < cols; columns r in [rows, rows_pad)
-// of `out` are zero-filled.  r' = r, or token_position(r) when `permute` is set (the
-// token order of the X^T G operands; rows_pad must then be a multiple of 128).
+// of `out` are zero-filled.  r' = r, or, when `permute` is set, the place of token r in the
+// permuted, blocked token order of the X^T G operands (ldo = tokens per block, block b of
+// all `cols` feature rows starts at b*cols*ldo; rows_pad must then be a multiple of 128).
 // 64 x 64 tiles through LDS, 256 threads.
 // grid = (ceil(rows_pad/64), ceil(cols/64), batch)
 template <typename Tin, typename Tout>
@@ -35,13 +36,20 @@ __global__ __launch_bounds__(256) void transpose_kernel(const Tin* __restrict__ 
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int c = c0 + ty + 4 * i, r = r0 + tx;
-    if (c < cols && r < rows_pad)
-      out[(int64_t)c * ldo + (permute ? token_position(r) : (int64_t)r)] = from_float<Tout>(tile[tx][ty + 4 * i]);
+    if (c < cols && r < rows_pad) {
+      int64_t o = (int64_t)c * ldo + r;
+      if (permute) {  // token order and token blocks of the X^T G operands; ldo = block length
+        const int64_t p = token_position(r), blk = p / ldo;
+        o = blk * cols * ldo + (int64_t)c * ldo + (p - blk * ldo);
+      }
+      out[o] = from_float<Tout>(tile[tx][ty + 4 * i]);
+    }
   }
 }
 
-// The token-minor, token-permuted copy of X for 2-byte elements, with 16-byte global
-// accesses on both sides: out[c*ldo + token_position(r)] = in[r*ldi + c].
+// The token-minor, token-permuted, token-blocked copy of X for 2-byte elements, with
+// 16-byte global accesses on both sides (layout as described at EpiGrad; ldo = tokens per
+// block, a multiple of 128).
 // tile = 128 rows (one token group) x 64 cols; each thread moves four 16-byte chunks in
 // and four out.  Needs cols % 64 == 0, rows_pad % 128 == 0, ldi % 8 == 0, ldo % 8 == 0.
 // grid = (ceil(rows_pad/128), cols/64, batch)
@@ -49,12 +57,13 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
                                                           int64_t in_batch_stride,
                                                           uint16_t* __restrict__ out, int64_t ldo,
                                                           int64_t out_batch_stride, int rows,
-                                                          int rows_pad) {
+                                                          int rows_pad, int cols) {
   constexpr int PITCH = 33;  // dwords per tile row (64 elements + 1 dword of skew)
   __shared__ uint32_t tile[128 * PITCH];
   const int r0 = blockIdx.x * 128, c0 = blockIdx.y * 64;
   in += (int64_t)blockIdx.z * in_batch_stride;
-  out += (int64_t)blockIdx.z * out_batch_stride;
+  // ldo = tokens per block; the 128-token group r0 lies in block r0 / ldo
+  out += (int64_t)blockIdx.z * out_batch_stride + (int64_t)(r0 / ldo) * cols * ldo + (r0 % ldo);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int c = threadIdx.x + i * 256;
@@ -81,7 +90,7 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
         w[e] = lo | (hi << 16);
       }
       intx4 v = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-      *reinterpret_cast<intx4*>(out + (int64_t)(c0 + f) * ldo + r0 + t8 * 8) = v;
+      *reinterpret_cast<intx4*>(out + (int64_t)(c0 + f) * ldo + t8 * 8) = v;
     }
   }
 }

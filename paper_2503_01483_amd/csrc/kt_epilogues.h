@@ -73,6 +73,8 @@ struct EpiMoments : EpiBase {
 // ADJACENT in memory: one 8-byte store per feature instead of four 2-byte ones, and 32
 // lanes cover 256 contiguous bytes.  Tokens in [n_tokens, ldt) are written as zero so the
 // padded K range contributes nothing; ldt is a multiple of 128.
+// Rows are stored in blocks of tb tokens (tb a multiple of 128): position p of feature f
+// lives at  (p / tb) * d * tb + f * tb + p % tb  (one block, tb = ldt, is the plain layout).
 __host__ __device__ __forceinline__ int64_t token_position(int64_t t) {
   return (t & ~(int64_t)127) + ((t & 31) << 2) + ((t & 127) >> 5);
 }
@@ -82,7 +84,7 @@ struct EpiGrad : EpiBase {
   using T = typename TL::T;
   const floatx4* coef;
   T* GT;
-  int64_t ldt;
+  int64_t ldt, tb, batch_stride;
   int n_tokens, d;
   static_assert(TL::BN % 128 == 0 && (TL::WTN == 128 || TL::WTN == 64), "token groups are 128 wide");
   __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
@@ -94,6 +96,8 @@ struct EpiGrad : EpiBase {
     if (group0 >= ldt) return;
     // lane's tokens: wave_tok0 + nb*32 + (lane & 31); positions are consecutive in nb
     const int64_t pos0 = group0 + ((f.lane & 31) << 2) + ((wave_tok0 & 127) >> 5);
+    const int64_t blk = pos0 / tb;
+    T* out = GT + (int64_t)batch * batch_stride + blk * d * tb + (pos0 - blk * tb);
     float alpha[TL::NB], mu[TL::NB], beta[TL::NB], m3[TL::NB];
 #pragma unroll
     for (int nb = 0; nb < TL::NB; ++nb) {
@@ -116,7 +120,7 @@ struct EpiGrad : EpiBase {
             v[nb] = from_float<T>(g);
           }
           const int feat = m0 + f.m_of(mb, r);
-          *reinterpret_cast<vecT*>(GT + ((int64_t)batch * d + feat) * ldt + pos0) = v;
+          *reinterpret_cast<vecT*>(out + (int64_t)feat * tb) = v;
         }
       }
     }

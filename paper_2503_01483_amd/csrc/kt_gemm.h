@@ -128,7 +128,13 @@ __device__ __forceinline__ void lds_barrier() {
 
 // Main loop.  Rows of A beyond M (and of B beyond N) are read from the last valid
 // row, so every load stays inside the operand; the epilogue masks them out.
-// The K range [k0, k0 + k_slabs*BK) must lie inside both operands' rows, and
+// K is addressed in slabs: slab g of an operand row starts at byte
+//   (g / slabs_per_block) * block_bytes + (g % slabs_per_block) * 128
+// of the row, which is the plain g * 128 for an ordinary row-major operand
+// (slabs_per_block = number of slabs in a row) and lets the token-minor operands of
+// dR = X^T G be stored in blocks of a few thousand tokens, so that the 256 rows a tile
+// reads at any one time lie within a couple of MiB instead of 256 separate pages.
+// The slab range [slab0, slab0 + k_slabs) must lie inside both operands' rows, and
 // (BM-1)*lda*sizeof(T) + 128 (same for B) must fit 32 bits (the host checks this).
 //
 // Schedule.  One K slab = 4 sub-steps of MB*NB MFMA "slots".  Everything that is not
@@ -148,7 +154,9 @@ template <class TL>
 __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__ A, int64_t lda,
                                               int M, int m0,
                                               const typename TL::T* __restrict__ B, int64_t ldb,
-                                              int N, int n0, int64_t k0, int k_slabs,
+                                              int N, int n0, int slab0, int k_slabs,
+                                              int slabs_per_block, int64_t block_bytes_a,
+                                              int64_t block_bytes_b,
                                               floatx16 (&acc)[TL::MB][TL::NB], char* lds) {
   using T = typename TL::T;
   constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
@@ -167,8 +175,17 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   const int lchunk = tid & 7;
 
   // global addressing: uniform 64-bit base (advanced per slab) + 32-bit byte offsets
-  const char* Ab = reinterpret_cast<const char*>(A + (int64_t)m0 * lda + k0);
-  const char* Bb = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb + k0);
+  const char* Ab = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+  const char* Bb = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
+  // byte offsets of K slab `slab` (relative to slab0) inside a row of A / of B: uniform values
+  int64_t ka = 0, kb = 0;
+  auto locate = [&](int slab) __attribute__((always_inline)) {
+    const int g = slab0 + slab;
+    const int blk = g / slabs_per_block;
+    const int64_t in_blk = (int64_t)(g - blk * slabs_per_block) * kRowBytes;
+    ka = blk * block_bytes_a + in_blk;
+    kb = blk * block_bytes_b + in_blk;
+  };
   uint32_t og[NLD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
@@ -198,13 +215,10 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   intx4 rg[NLD];        // one K slab in flight from global memory
   intx4 fr[2][NFRAG];   // MFMA fragments, double buffered: [buf][0..MB) = A, [MB..) = B
 
-  auto gload = [&](auto i_c, int slab) __attribute__((always_inline)) {
+  // loads chunk i of the slab last passed to locate()
+  auto gload = [&](auto i_c) __attribute__((always_inline)) {
     constexpr int i = decltype(i_c)::value;
-#ifdef KT_EXP_NOADV
-    const char* base = (i < A_LD ? Ab : Bb) + (int64_t)(slab & 1) * kRowBytes;
-#else
-    const char* base = (i < A_LD ? Ab : Bb) + (int64_t)slab * kRowBytes;
-#endif
+    const char* base = i < A_LD ? Ab + ka : Bb + kb;
     rg[i] = *reinterpret_cast<const intx4*>(base + og[i]);
   };
   auto lstore = [&](auto i_c, auto stage_c) __attribute__((always_inline)) {
@@ -237,7 +251,7 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
     constexpr bool MORE = true, LOAD2 = true;
     using Cur = std::integral_constant<int, PAR>;
     using Nxt = std::integral_constant<int, PAR ^ 1>;
-    const int slab2 = slab + 2 < k_slabs ? slab + 2 : k_slabs - 1;
+    locate(slab + 2 < k_slabs ? slab + 2 : k_slabs - 1);
     static_for<4 * NMMA>([&](auto g_c) __attribute__((always_inline)) {
       constexpr int g = decltype(g_c)::value;  // slot index inside the slab
       constexpr int s = g / NMMA, j = g % NMMA;
@@ -266,7 +280,7 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
           if constexpr (MORE) lstore(i_c, Nxt{});
 #endif
 #ifndef KT_EXP_NOGLOAD
-          if constexpr (LOAD2) gload(i_c, slab2);
+          if constexpr (LOAD2) gload(i_c);
 #endif
         }
       });
@@ -277,10 +291,11 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   using P1 = std::integral_constant<int, 1>;
 
   // prologue: slab 0 -> LDS stage 0, slab 1 -> registers, first fragments -> buffer 0
-  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { gload(i_c, 0); });
+  locate(0);
+  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { gload(i_c); });
   static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { lstore(i_c, P0{}); });
-  const int slab1 = k_slabs > 1 ? 1 : 0;
-  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { gload(i_c, slab1); });
+  locate(k_slabs > 1 ? 1 : 0);
+  static_for<NLD>([&](auto i_c) __attribute__((always_inline)) { gload(i_c); });
   lds_barrier();
   static_for<NFRAG>([&](auto i_c) __attribute__((always_inline)) { fread(P0{}, i_c, P0{}, C0{}); });
   __builtin_amdgcn_sched_barrier(0);
@@ -306,6 +321,8 @@ struct GemmShape {
   int slabs_per_split;
   int tiles_total;   // tiles_m * tiles_n * split_k
   int grid_padded;   // tiles_total rounded up to a multiple of 8
+  int slabs_per_block;             // K blocking of the operand rows (see gemm_mainloop)
+  int64_t block_bytes_a, block_bytes_b;
 };
 
 // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them,
@@ -354,7 +371,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmShape g, Epi epi) {
 
   const T* A = static_cast<const T*>(g.A) + (int64_t)batch * g.batch_stride_a;
   const T* B = static_cast<const T*>(g.B) + (int64_t)batch * g.batch_stride_b;
-  gemm_mainloop<TL>(A, g.lda, g.M, m0, B, g.ldb, g.N, n0, (int64_t)slab0 * TL::BK, slabs, acc, lds);
+  gemm_mainloop<TL>(A, g.lda, g.M, m0, B, g.ldb, g.N, n0, slab0, slabs, g.slabs_per_block,
+                    g.block_bytes_a, g.block_bytes_b, acc, lds);
   epi(acc, batch, tm, tn, ks, m0, n0);
 }
 

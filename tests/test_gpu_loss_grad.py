@@ -26,7 +26,8 @@ def test_c1_tiny_fp32_full():
     check_loss_grad(g, o, TOL_F32)
 
 
-@pytest.mark.parametrize("n,d", [(1, 128), (63, 128), (64, 256), (65, 128), (257, 384), (1000, 256)])
+@pytest.mark.parametrize("n,d", [(1, 128), (63, 128), (64, 256), (65, 128), (257, 384), (1000, 256),
+                                  (4500, 128)])  # > 4096 tokens: two token blocks
 def test_fp32_ragged_shapes(n, d):
     X = ktgen.make_x(n, d, seed=n + d, outlier_cols=3, outlier_scale=30.0, t_frac=0.05, dtype="f32")
     R = ktgen.random_orthogonal(d, seed=d)
@@ -34,7 +35,8 @@ def test_fp32_ragged_shapes(n, d):
 
 
 @pytest.mark.parametrize("n,d,batch", [(1, 128, 1), (200, 128, 3), (777, 256, 1), (1000, 384, 2),
-                                        (520, 512, 1), (2048, 768, 1), (300, 1024, 1)])
+                                        (520, 512, 1), (2048, 768, 1), (300, 1024, 1),
+                                        (9000, 256, 1), (4200, 128, 2)])  # several token blocks
 def test_bf16_shapes(n, d, batch):
     xs = [ktgen.make_x(n, d, seed=7 * b + n, outlier_cols=4, outlier_scale=60.0, t_frac=0.05,
                        dtype="bf16") for b in range(batch)]
