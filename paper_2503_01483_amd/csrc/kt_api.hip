@@ -8,6 +8,7 @@
 
 #include "../../include/kt.h"
 #include "kt_aux.h"
+#include "kt_fused_d128.h"
 
 namespace kt {
 
@@ -122,6 +123,8 @@ struct Carver {
 };
 
 struct LossGradPlan {
+  bool fused;      // d = 128 bf16: single-pass kernel, no token-minor copies
+  int fused_wgs;   // workgroups per problem on the fused path
   bool fp32;
   size_t esz;
   int64_t ldt;     // padded token count of the token-minor copies (multiple of 128)
@@ -138,6 +141,22 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   LossGradPlan p;
   p.fp32 = (xdt == KT_F32);
   p.esz = p.fp32 ? 4 : 2;
+  p.fused = !p.fp32 && d == 128;
+  p.fused_wgs = 0;
+  if (p.fused) {
+    const int64_t tiles = ceil_div(n, 256);
+    int64_t wgs = ceil_div(kNumCUs, batch);  // about one workgroup per CU over all problems
+    p.fused_wgs = (int)(wgs < tiles ? wgs : tiles);
+    p.ldt = p.tb = p.nblk = 0;
+    p.P = p.tiles_dd = p.slabs_per_split = p.split_k = p.loss_blocks = 0;
+    Carver c;
+    p.o_rt = c.take((size_t)batch * d * d * p.esz);
+    p.o_losspart = c.take((size_t)batch * p.fused_wgs * 8);
+    p.o_splitk = c.take((size_t)p.fused_wgs * batch * d * d * 4);
+    p.o_part = p.o_coef = p.o_xt = p.o_gt = 0;
+    p.total = c.off;
+    return p;
+  }
   p.ldt = round_up(n, 128);
   p.tb = p.ldt < kTokenBlock ? p.ldt : kTokenBlock;
   p.nblk = ceil_div(p.ldt, p.tb);
@@ -357,6 +376,41 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   return KT_OK;
 }
 
+// d = 128, bf16: one pass over X (kt_fused_d128.h), then fixed-order reductions.
+static kt_status run_loss_grad_fused(const LossGradPlan& p, const void* X, int64_t ldx, const void* R,
+                                     int64_t ldr, kt_dtype rdt, int64_t batch, int64_t n, int64_t d,
+                                     float kappa_target, float* loss, float* row_kurt, float* dR,
+                                     char* ws, hipStream_t st) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fused_d128_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kF128LdsBytes) != hipSuccess)
+      return fail(KT_ERR_DEVICE, "the fused d=128 kernel needs %d bytes of LDS per workgroup", kF128LdsBytes);
+    attr_done = true;
+  }
+  bf16* RT = reinterpret_cast<bf16*>(ws + p.o_rt);
+  double* loss_part = reinterpret_cast<double*>(ws + p.o_losspart);
+  float* dR_part = reinterpret_cast<float*>(ws + p.o_splitk);
+  if (!prep_rt<bf16>(R, ldr, rdt, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
+  {
+    ProfScope prof(0, st);
+    hipLaunchKernelGGL(fused_d128_kernel, dim3(p.fused_wgs, (unsigned)batch), dim3(256), kF128LdsBytes, st,
+                       static_cast<const bf16*>(X), ldx, n * ldx, RT, (int)n, kappa_target, row_kurt,
+                       loss_part, dR_part, dR ? 1 : 0);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "fused kernel launch failed");
+  }
+  hipLaunchKernelGGL(finalize_loss_kernel, dim3((unsigned)batch), dim3(256), 0, st, loss_part, p.fused_wgs,
+                     (int)n, loss);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "finalize_loss launch failed");
+  if (dR) {
+    const int64_t count = batch * d * d;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(ceil_div(count, 256) < 4096 ? ceil_div(count, 256) : 4096)),
+                       dim3(256), 0, st, dR_part, count, p.fused_wgs, dR, count);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "partial dR reduce launch failed");
+  }
+  return KT_OK;
+}
+
 // ------------------------------------------------------------------ fake-quant ----
 template <typename T, class TFWD, class TQ>
 static kt_status run_quant(const QuantPlan& p, const void* X, int64_t ldx, const void* R, int64_t ldr,
@@ -441,6 +495,9 @@ kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64
   if (s != KT_OK) return s;
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p.fused)
+    return run_loss_grad_fused(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss, row_kurt, dR,
+                               ws, st);
   if (p.fp32)
     return run_loss_grad<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss,
                                         row_kurt, dR, ws, st);

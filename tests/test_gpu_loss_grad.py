@@ -137,3 +137,35 @@ def test_c2_shape_chunk_vs_oracle_and_additivity():
         lacc += 640 * part["loss"][0]
     assert rel_fro(2560 * full["dR"][0], acc) < 5e-3      # bf16 rounding of dL/dY differs per 1/n
     assert abs(2560 * full["loss"][0] - lacc) <= 1e-5 * lacc
+
+
+# ---- head-dimension problems (d = 128, bf16) take the single-pass fused kernel -------------------
+@pytest.mark.parametrize("n,batch,kt_", [(255, 1, 0.0), (256, 2, 0.0), (257, 1, 0.0), (3000, 5, 0.0),
+                                          (20000, 1, 0.0), (1500, 2, 2.6)])
+def test_fused_d128_against_oracle(n, batch, kt_):
+    X, R, cfg = ktgen.make_problem("C4", seed=n, n=n, batch=batch)
+    if kt_ > 0:
+        X[:, ::3] = (torch.rand(batch, (n + 2) // 3, 128) * 2 - 1).to(X.dtype)   # rows below the target too
+    o = oracle_loss_grad(X, R, kappa_target=kt_)
+    if kt_ > 0:
+        assert (o["row_kurt"] > kt_).any() and (o["row_kurt"] < kt_).any()
+    g = gpu_loss_grad(X, R, kappa_target=kt_)
+    check_loss_grad(g, o, TOL_BF16)
+    # loss-only call gives the same loss and row values
+    g2 = gpu_loss_grad(X, R, kappa_target=kt_, want_dR=False)
+    assert np.array_equal(g2["loss"], g["loss"]) and np.array_equal(g2["row_kurt"], g["row_kurt"])
+
+
+def test_fused_d128_degenerate_rows_and_determinism():
+    d = 128
+    H = torch.tensor(scipy.linalg.hadamard(d) / np.sqrt(d), dtype=torch.float32)
+    X = torch.eye(d)[:100].to(torch.bfloat16)
+    X[99] = 0
+    g = gpu_loss_grad(X, H)
+    o = oracle_loss_grad(X, H)
+    assert g["row_kurt"][0, 0] == 0.0 and g["row_kurt"][0, 99] == 0.0
+    assert np.allclose(g["row_kurt"], o["row_kurt"], atol=1e-5)
+    assert abs(g["loss"][0] - o["loss"][0]) < 1e-5 and np.abs(g["dR"]).max() < 1e-6
+    X2, R2, _ = ktgen.make_problem("C4", seed=5, n=10000, batch=3)
+    a, b = gpu_loss_grad(X2, R2), gpu_loss_grad(X2, R2)
+    assert np.array_equal(a["dR"], b["dR"]) and np.array_equal(a["loss"], b["loss"])
