@@ -144,7 +144,7 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   p.fused = !p.fp32 && d == 128;
   p.fused_wgs = 0;
   if (p.fused) {
-    const int64_t tiles = ceil_div(n, 256);
+    const int64_t tiles = ceil_div(n, kF128Tile);
     int64_t wgs = ceil_div(kNumCUs, batch);  // about one workgroup per CU over all problems
     p.fused_wgs = (int)(wgs < tiles ? wgs : tiles);
     p.ldt = p.tb = p.nblk = 0;

@@ -4,7 +4,7 @@
 // For many small independent problems (one 128 x 128 rotation per KV head and layer, the
 // R2 learner of "Learning the Rotations") the three-GEMM path is bandwidth-bound: it
 // reads X three times and writes and re-reads two token-minor copies.  Here a workgroup
-// walks token tiles of 256 rows of one problem and, per tile,
+// walks token tiles of 128 rows of one problem and, per tile,
 //   B. Y = X_tile R            (MFMA; token on the lane, all 128 features of a token in the
 //                               registers of one lane pair)
 //   C. per-token mean, centred moments (two-pass, fp32), kurtosis, loss term,
@@ -17,17 +17,22 @@
 // Partial dR and loss sums of the workgroups of a problem are added by fixed-order
 // reduction kernels afterwards.
 //
-// LDS (160 KiB): R^T 32 KiB | X tile 64 KiB | G tile 64 KiB, rows of 256 bytes.
-//  R^T and X: 16-byte chunks XOR-swizzled with (row & 15) -> conflict-free fragment reads.
+// LDS (160 KiB): three X tiles and two G tiles of 32 KiB, rows of 256 bytes (X(i+2) arrives
+// while E reads X(i) and B reads X(i+1); stage E of one tile overlaps stages C-D of the next);
+// R^T lives in registers.
+//  X: 16-byte chunks XOR-swizzled with (row & 15) -> conflict-free fragment reads.
 //  G: 8-byte units XOR-swizzled with swz(t) = 4*(t%8) + (t/8)%4 -> conflict-free 8-byte
 //  stores from 32 token lanes and conflict-free transposing reads.
 #pragma once
 #include "kt_aux.h"
+#include "kt_gemm.h"
 
 namespace kt {
 
-constexpr int kF128RtOff = 0, kF128XOff = 32768, kF128GOff = 32768 + 65536;
-constexpr int kF128LdsBytes = 32768 + 65536 + 65536;
+constexpr int kF128Tile = 128;                  // tokens per tile
+constexpr int kF128BufBytes = kF128Tile * 256;  // one X or G tile: 128 rows of 256 bytes
+constexpr int kF128GOff = 3 * kF128BufBytes;     // LDS: X[3] | G[2]
+constexpr int kF128LdsBytes = 5 * kF128BufBytes;  // 160 KiB
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
@@ -44,8 +49,49 @@ __device__ __forceinline__ intx4 read_tr_operand(const char* lds, int addr_lo, i
   return __builtin_bit_cast(intx4, v);
 }
 
+// The matrix-core instructions of this kernel are written as inline assembly so that the
+// register file of every operand is fixed: R^T fragments and the dR accumulators live in
+// accumulation registers (only the matrix core touches them), Y and the LDS fragments in
+// vector registers (the vector ALU consumes Y).  Left to the register allocator the 256
+// registers of R^T and accumulators get shuffled between the two files every tile.
+// The compiler does not know these are matrix instructions: results are read by other
+// instruction types only behind mfma_result_fence().
+__device__ __forceinline__ void mfma_y_first(floatx16& y, const intx4& rt, const intx4& x) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(y) : "a"(rt), "v"(x));
+}
+__device__ __forceinline__ void mfma_y(floatx16& y, const intx4& rt, const intx4& x) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(y) : "a"(rt), "v"(x));
+}
+__device__ __forceinline__ void mfma_dr(floatx16& acc, const intx4& xt, const intx4& gt) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(xt), "v"(gt));
+}
+// An 8-pass matrix instruction must be 11 issue slots old before another instruction type
+// reads its result.
+__device__ __forceinline__ void mfma_result_fence(floatx16& a, floatx16& b, floatx16& c, floatx16& d) {
+  asm volatile("s_nop 15" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+__device__ __forceinline__ void mfma_result_fence_acc(floatx16& a, floatx16& b, floatx16& c, floatx16& d) {
+  asm volatile("s_nop 15" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_addr + 16 l
+// (lds_addr is wave-uniform).  Written as assembly so that the compiler does not tie later LDS
+// reads to these loads with a full wait; the waits are placed by hand (vmcnt).
+__device__ __forceinline__ void load_to_lds_16(const void* src, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr)
+               : "memory");
+}
+
 // grid = (S, batch): S workgroups share the token tiles of one problem.
 // dR_part[(wg * batch + b) * 128*128 + k*128 + j], loss_part[b * S + wg].
+//
+// Software pipeline over the tiles i = 0, 1, ... of a workgroup (one barrier per tile).
+// X(i) lives in X buffer i % 3, G(i) in G buffer i & 1.  Iteration i:
+//   request X(i+2) (global -> LDS, buffer last read by E(i-1)); wait for X(i+1)
+//   B(i+1): Y = X R on the wave's own 32 rows (it moved those rows itself: no barrier)
+//   E(i) and C/D(i+1) as ONE instruction stream: one matrix instruction of
+//     dR += X(i)^T G(i) every ~20 vector instructions of the statistics / dL/dY arithmetic
+//   barrier (G(i+1) complete for every wave; buffers of tile i free)
 __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restrict__ X, int64_t ldx,
                                                          int64_t x_batch_stride,
                                                          const __bf16* __restrict__ RT, int n,
@@ -54,39 +100,53 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
                                                          double* __restrict__ loss_part,
                                                          float* __restrict__ dR_part, int want_grad) {
   extern __shared__ __align__(16) char lds[];
-  constexpr int D = 128;
+  constexpr int D = 128, T = kF128Tile, BUF = kF128BufBytes;
+  using std::integral_constant;
   const int b = blockIdx.y, S = gridDim.x, wg = blockIdx.x, batch = gridDim.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5, l32 = lane & 31;
   const int wm2 = wave >> 1, wn2 = wave & 1;  // dR quadrant of this wave in stage E
   X += (int64_t)b * x_batch_stride;
   RT += (int64_t)b * D * D;
-  const int tiles = (n + 255) / 256;
+  const int tiles = (n + T - 1) / T;
+  const int my_tiles = wg < tiles ? (tiles - wg + S - 1) / S : 0;  // tiles wg, wg+S, ...
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
 
-  // R^T -> LDS (8 chunks of 16 bytes per thread)
+  // R^T fragments for all 8 K sub-steps and 4 feature blocks: 128 registers, loaded once
+  intx4 rtf[8][4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int c = tid + i * 256, row = c >> 4, ch = c & 15;
-    const intx4 v = *reinterpret_cast<const intx4*>(RT + row * D + ch * 8);
-    *reinterpret_cast<intx4*>(lds + kF128RtOff + row * 256 + ((ch ^ (row & 15)) << 4)) = v;
-  }
-
-  intx4 xr[16];  // one X tile in flight: 16 chunks of 16 bytes per thread
-  auto gload_tile = [&](int tile) __attribute__((always_inline)) {
+  for (int s = 0; s < 8; ++s)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int c = tid + i * 256, row = c >> 4, ch = c & 15;
-      const int token = tile * 256 + row;
-      intx4 v = {0, 0, 0, 0};
-      if (token < n) v = *reinterpret_cast<const intx4*>(X + (int64_t)token * ldx + ch * 8);
-      xr[i] = v;
+    for (int mb = 0; mb < 4; ++mb) {
+      rtf[s][mb] = *reinterpret_cast<const intx4*>(RT + (mb * 32 + l32) * D + (2 * s + half) * 8);
+      asm volatile("" : "+a"(rtf[s][mb]));
     }
-  };
-  auto store_tile = [&]() __attribute__((always_inline)) {
+
+  // X tile movement: a wave owns rows 32*wave .. +31 of the tile and moves them with 8
+  // instructions of 4 rows (1 KiB) each.  The 16-byte swizzle is applied on the source side:
+  // LDS chunk position (l & 15) of row r receives global chunk (l & 15) ^ (r & 15).
+  const int xrow0 = wave * 32 + (lane >> 4);  // tile row of instruction 0; instruction i: + 4 i
+  const __bf16* xlane[4];                     // source of instruction i at tile 0: xlane[i & 3] + 4 i ldx
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int c = tid + i * 256, row = c >> 4, ch = c & 15;
-      *reinterpret_cast<intx4*>(lds + kF128XOff + row * 256 + ((ch ^ (row & 15)) << 4)) = xr[i];
+  for (int i = 0; i < 4; ++i)
+    xlane[i] = X + (int64_t)xrow0 * ldx + (((lane & 15) ^ ((4 * i + (lane >> 4)) & 15)) << 3);
+  auto load_tile = [&](int tile, int buf) __attribute__((always_inline)) {
+    const unsigned dst = lds_base + buf * BUF + wave * (32 * 256);
+    const int64_t tile_off = (int64_t)tile * T * ldx;
+    if (tile * T + T <= n) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        load_to_lds_16(xlane[i & 3] + tile_off + (int64_t)(4 * i) * ldx, dst + i * 1024);
+    } else {  // last, partial tile: rows past the end are zero-filled
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (tile * T + xrow0 + 4 * i < n)
+          load_to_lds_16(xlane[i & 3] + tile_off + (int64_t)(4 * i) * ldx, dst + i * 1024);
+        else
+          *reinterpret_cast<intx4*>(lds + buf * BUF + wave * (32 * 256) + i * 1024 + lane * 16) =
+              intx4{0, 0, 0, 0};
+      }
     }
   };
 
@@ -94,152 +154,214 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc2[i][j][r] = 0.f;
+      asm volatile("" : "+a"(acc2[i][j]));
+    }
   double loss_acc = 0.0;
   const float inv_d = 1.0f / (float)D;
   const float grad_scale = 4.0f / ((float)n * (float)D);
 
-  // lane constants of the transposing reads (stage E)
+  // lane constants of the transposing reads (stage E): token row 16 s + tr_tok (+4) of the tile
   const int g16 = lane >> 4, rr = lane & 15;
-  const int tr_feat = 16 * (g16 & 1) + 4 * (rr & 3);  // + block base: first of 4 features
-  const int tr_tok = 8 * (g16 >> 1) + (rr >> 2);      // + 16*s (+4): token row inside the tile
-
-  int tile = wg;
-  if (tile < tiles) gload_tile(tile);
-  for (; tile < tiles; tile += S) {
-    __syncthreads();  // everyone is done with the previous X and G tiles (and R^T is stored)
-    store_tile();
-    if (tile + S < tiles) gload_tile(tile + S);
-    __syncthreads();
-
-    // ---- B: Y^T (features x this wave's 64 tokens) = R^T X_tile^T -------------------
-    floatx16 acc[4][2];
+  const int tr_feat = 16 * (g16 & 1) + 4 * (rr & 3);
+  const int tr_tok = 8 * (g16 >> 1) + (rr >> 2);
+  int xa_lo[2], xa_hi[2], gb_lo[2][2], gb_hi[2][2];  // G: [parity of s][block]
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+  for (int ib = 0; ib < 2; ++ib) {
+    const int u = (wm2 * 64 + ib * 32 + tr_feat) >> 2;  // 8-byte unit inside the X row
+    const int sel = (u & 1) << 3, ch = u >> 1, t_hi = tr_tok + 4;
+    xa_lo[ib] = tr_tok * 256 + (((ch ^ (tr_tok & 15)) << 4) | sel);
+    xa_hi[ib] = t_hi * 256 + (((ch ^ (t_hi & 15)) << 4) | sel);
+  }
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+  for (int par = 0; par < 2; ++par)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const int coff = ((2 * s + half) ^ (l32 & 15)) << 4;
-      intx4 a[4], bb[2];
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-        a[mb] = *reinterpret_cast<const intx4*>(lds + kF128RtOff + (mb * 32 + l32) * 256 + coff);
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        bb[nb] = *reinterpret_cast<const intx4*>(lds + kF128XOff + (wave * 64 + nb * 32 + l32) * 256 + coff);
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) Mma<__bf16>::run(a[mb], bb[nb], acc[mb][nb]);
+    for (int jb = 0; jb < 2; ++jb) {
+      const int u = (wn2 * 64 + jb * 32 + tr_feat) >> 2;
+      const int t_lo = 16 * par + tr_tok, t_hi = t_lo + 4;
+      const int z_lo = ((t_lo & 7) << 2) | ((t_lo >> 3) & 3), z_hi = ((t_hi & 7) << 2) | ((t_hi >> 3) & 3);
+      gb_lo[par][jb] = tr_tok * 256 + ((u ^ z_lo) << 3);
+      gb_hi[par][jb] = (tr_tok + 4) * 256 + ((u ^ z_hi) << 3);
     }
 
-    // ---- C, D: per-token statistics and dL/dY ------------------------------------------
+  floatx16 acc[4];  // Y^T of the tile in flight: 64 of the 128 features of this lane's token
+
+  // B: Y^T (128 features x this wave's 32 tokens) = R^T X^T from X buffer `buf`
+  auto stage_b = [&](int buf) __attribute__((always_inline)) {
+    const char* xrow = lds + buf * BUF + (wave * 32 + l32) * 256;
+    intx4 xb[2];
+    xb[0] = *reinterpret_cast<const intx4*>(xrow + (((0 + half) ^ (l32 & 15)) << 4));
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int tok_local = wave * 64 + nb * 32 + l32;
-      const int token = tile * 256 + tok_local;
+    for (int s = 0; s < 8; ++s) {
+      if (s + 1 < 8)
+        xb[(s + 1) & 1] = *reinterpret_cast<const intx4*>(xrow + (((2 * (s + 1) + half) ^ (l32 & 15)) << 4));
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        if (s == 0)
+          mfma_y_first(acc[mb], rtf[0][mb], xb[0]);
+        else
+          mfma_y(acc[mb], rtf[s][mb], xb[s & 1]);
+      }
+    }
+    mfma_result_fence(acc[0], acc[1], acc[2], acc[3]);
+  };
+
+  // C, D of tile `tile` (statistics of this lane's token, dL/dY -> G buffer gbuf_w) with the 32
+  // matrix instructions of E (X buffer xbuf_r, G buffer gbuf_r) dealt between the arithmetic.
+  // WITH_CD / WITH_E switch the two halves off for the first and last tile of a workgroup.
+  auto stage_cde = [&](auto with_cd_c, auto with_e_c, int tile, int gbuf_w, int xbuf_r,
+                       int gbuf_r) __attribute__((always_inline)) {
+    constexpr bool WITH_CD = decltype(with_cd_c)::value, WITH_E = decltype(with_e_c)::value;
+    const char* xbase = lds + xbuf_r * BUF;
+    const char* gbase = lds + kF128GOff + gbuf_r * BUF;
+    intx4 fa[2][2], fb[2][2];
+    auto fread = [&](auto s_c) __attribute__((always_inline)) {
+      constexpr int s = decltype(s_c)::value;
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib)
+        fa[s & 1][ib] = read_tr_operand(xbase, xa_lo[ib] + s * 16 * 256, xa_hi[ib] + s * 16 * 256);
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+        fb[s & 1][jb] = read_tr_operand(gbase, gb_lo[s & 1][jb] + s * 16 * 256, gb_hi[s & 1][jb] + s * 16 * 256);
+    };
+    // matrix instruction k of E: K sub-step k / 4, dR block (k / 2) & 1, k & 1
+    auto tick = [&](auto k_c) __attribute__((always_inline)) {
+      if constexpr (WITH_E) {
+        constexpr int k = decltype(k_c)::value, s = k >> 2, ib = (k >> 1) & 1, jb = k & 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr ((k & 3) == 0 && s + 1 < 8) fread(integral_constant<int, s + 1>{});
+        mfma_dr(acc2[ib][jb], fa[s & 1][ib], fb[s & 1][jb]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    if constexpr (WITH_E) fread(integral_constant<int, 0>{});
+    if constexpr (!WITH_CD) {
+      static_for<32>(tick);
+    } else {
+      const int tok_local = wave * 32 + l32;
+      const int token = tile * T + tok_local;
       const bool valid = token < n;
       float s1 = 0.f;
+      static_for<4>([&](auto mb_c) __attribute__((always_inline)) {
+        constexpr int mb = decltype(mb_c)::value;
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s1 += acc[mb][nb][r];
+        for (int r = 0; r < 16; ++r) s1 += acc[mb][r];
+        tick(integral_constant<int, mb>{});
+      });
       s1 += __shfl_xor(s1, 32);
       const float mu = s1 * inv_d;
       float s2 = 0.f, s3 = 0.f, s4 = 0.f;
+      static_for<16>([&](auto g_c) __attribute__((always_inline)) {
+        constexpr int g = decltype(g_c)::value, mb = g >> 2, q = g & 3;
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float c = acc[mb][nb][r] - mu;
-          acc[mb][nb][r] = c;
+        for (int e = 0; e < 4; ++e) {
+          const float c = acc[mb][4 * q + e] - mu;
+          acc[mb][4 * q + e] = c;
           const float c2 = c * c;
           s2 += c2;
           s3 = fmaf(c2, c, s3);
           s4 = fmaf(c2, c2, s4);
         }
+        tick(integral_constant<int, 4 + g>{});
+      });
       s2 += __shfl_xor(s2, 32);
       s3 += __shfl_xor(s3, 32);
       s4 += __shfl_xor(s4, 32);
+      tick(integral_constant<int, 20>{});
       const float m2 = s2 * inv_d, m3 = s3 * inv_d, m4 = s4 * inv_d;
       const bool ok = valid && m2 > 1e-5f * (m2 + mu * mu);
-      float kappa = 0.f, alpha = 0.f, beta = 0.f, term = 0.f;
-      if (ok) {
-        kappa = m4 / (m2 * m2);
-        float sgn = 1.f;
-        if (kappa_target != 0.f) {
-          const float dk = kappa - kappa_target;
-          sgn = (float)((dk > 0.f) - (dk < 0.f));
-          term = fabsf(dk);
-        } else {
-          term = kappa;
-        }
-        alpha = sgn * grad_scale / (m2 * m2);
-        beta = kappa * m2;
-      } else if (valid && kappa_target != 0.f) {
-        term = fabsf(kappa_target);
+      // branch-free: a degenerate or out-of-range token gets kappa = 0 and no gradient
+      const float m2s = ok ? m2 : 1.f;
+      const float inv_m2sq = 1.0f / (m2s * m2s);
+      const float kappa = ok ? m4 * inv_m2sq : 0.f;
+      float sgn = 1.f, term = kappa;
+      if (kappa_target != 0.f) {  // uniform
+        const float dk = kappa - kappa_target;
+        sgn = (float)((dk > 0.f) - (dk < 0.f));
+        term = fabsf(dk);
       }
-      if (half == 0 && valid) {
-        loss_acc += (double)term;
-        if (row_kurt) row_kurt[(int64_t)b * n + token] = kappa;
-      }
+      const float alpha = ok ? sgn * grad_scale * inv_m2sq : 0.f;
+      const float beta = kappa * m2;
+      loss_acc += (half == 0 && valid) ? (double)term : 0.0;
+      tick(integral_constant<int, 21>{});
       if (want_grad) {
         const int swz = ((tok_local & 7) << 2) | ((tok_local >> 3) & 3);
-        char* grow = lds + kF128GOff + tok_local * 256;
+        char* grow = lds + kF128GOff + gbuf_w * BUF + tok_local * 256;
+        static_for<16>([&](auto g_c) __attribute__((always_inline)) {
+          constexpr int g = decltype(g_c)::value, mb = g >> 2, q = g & 3;
+          typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+          bf16x4 v;
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-            bf16x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float c = acc[mb][nb][4 * q + e];
-              float g = alpha * fmaf(c, fmaf(c, c, -beta), -m3);
-              if (alpha == 0.f) g = 0.f;
-              v[e] = (__bf16)g;
-            }
-            const int u = mb * 8 + 2 * q + half;  // 8-byte unit: features 4u .. 4u+3
-            *reinterpret_cast<bf16x4*>(grow + ((u ^ swz) << 3)) = v;
+          for (int e = 0; e < 4; ++e) {
+            const float c = acc[mb][4 * q + e];
+            v[e] = (__bf16)(alpha * fmaf(c, fmaf(c, c, -beta), -m3));
           }
+          const int u = mb * 8 + 2 * q + half;  // 8-byte unit: features 4u .. 4u+3
+          *reinterpret_cast<bf16x4*>(grow + ((u ^ swz) << 3)) = v;
+          constexpr int k0 = 22 + (g * 10) / 16, k1 = 22 + ((g + 1) * 10) / 16;
+          if constexpr (k1 > k0) tick(integral_constant<int, k0>{});
+        });
+      } else {
+        static_for<10>([&](auto j_c) __attribute__((always_inline)) {
+          tick(integral_constant<int, 22 + decltype(j_c)::value>{});
+        });
       }
+      if (row_kurt && half == 0 && valid) row_kurt[(int64_t)b * n + token] = kappa;
     }
-    if (!want_grad) continue;
-    __syncthreads();
+  };
+  using Yes = std::true_type;
+  using No = std::false_type;
 
-    // ---- E: dR quadrant += X_tile^T G_tile, K = the tile's 256 tokens -------------------
-#pragma unroll 4
-    for (int s = 0; s < 16; ++s) {
-      const int t_lo = 16 * s + tr_tok, t_hi = t_lo + 4;
-      intx4 a[2], bb[2];
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
-        const int u = (wm2 * 64 + ib * 32 + tr_feat) >> 2;  // 8-byte unit inside the X row
-        const int sel = (u & 1) << 3, ch = u >> 1;
-        a[ib] = read_tr_operand(lds, kF128XOff + t_lo * 256 + (((ch ^ (t_lo & 15)) << 4) | sel),
-                                kF128XOff + t_hi * 256 + (((ch ^ (t_hi & 15)) << 4) | sel));
+  if (my_tiles > 0) {
+    load_tile(wg, 0);
+    if (my_tiles > 1) load_tile(wg + S, 1);
+    // vmcnt(8) leaves the 8 newest loads in flight; a partial tile issues fewer than 8
+    if (my_tiles > 1 && (wg + S) * T + T <= n)
+      __builtin_amdgcn_s_waitcnt(0x0F78);
+    else
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    asm volatile("" ::: "memory");
+    stage_b(0);
+    stage_cde(Yes{}, No{}, wg, 0, 0, 0);
+    lds_barrier();
+    int xcur = 0;
+    // advance to tile i+1: request X(i+2), wait for X(i+1), B(i+1); returns the X buffer of i+1
+    auto advance = [&](int i) __attribute__((always_inline)) {
+      const int xnxt = xcur == 2 ? 0 : xcur + 1, xnn = xnxt == 2 ? 0 : xnxt + 1;
+      const int t2 = wg + (i + 2) * S;
+      const bool more2 = i + 2 < my_tiles;
+      if (more2) load_tile(t2, xnn);  // buffer last read by E(i-1)
+      if (more2 && t2 * T + T <= n)
+        __builtin_amdgcn_s_waitcnt(0x0F78);  // X(i+1) landed, X(i+2) in flight
+      else
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+      asm volatile("" ::: "memory");
+      stage_b(xnxt);
+      return xnxt;
+    };
+    if (want_grad) {
+      for (int i = 0; i + 1 < my_tiles; ++i) {
+        const int xnxt = advance(i);
+        stage_cde(Yes{}, Yes{}, wg + (i + 1) * S, (i + 1) & 1, xcur, i & 1);
+        lds_barrier();
+        xcur = xnxt;
       }
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        const int u = (wn2 * 64 + jb * 32 + tr_feat) >> 2;
-        const int z_lo = ((t_lo & 7) << 2) | ((t_lo >> 3) & 3), z_hi = ((t_hi & 7) << 2) | ((t_hi >> 3) & 3);
-        bb[jb] = read_tr_operand(lds, kF128GOff + t_lo * 256 + ((u ^ z_lo) << 3),
-                                 kF128GOff + t_hi * 256 + ((u ^ z_hi) << 3));
+      stage_cde(No{}, Yes{}, 0, 0, xcur, (my_tiles - 1) & 1);
+    } else {
+      for (int i = 0; i + 1 < my_tiles; ++i) {
+        const int xnxt = advance(i);
+        stage_cde(Yes{}, No{}, wg + (i + 1) * S, (i + 1) & 1, xcur, i & 1);
+        lds_barrier();
+        xcur = xnxt;
       }
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb) Mma<__bf16>::run(a[ib], bb[jb], acc2[ib][jb]);
     }
   }
 
   // ---- wrap-up: partial dR and partial loss of this workgroup ----------------------------
   if (want_grad) {
+    mfma_result_fence_acc(acc2[0][0], acc2[0][1], acc2[1][0], acc2[1][1]);
     float* out = dR_part + ((int64_t)wg * batch + b) * (D * D);
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib)

@@ -75,3 +75,26 @@ def test_c3_full_size_step_is_orthogonal_and_descends():
     RtR = Rw[0].double().T @ Rw[0].double()
     assert float((RtR - torch.eye(d, dtype=torch.float64, device="cuda")).abs().max()) < 1e-6
     assert l1 < l0
+
+
+def test_c4_full_size_sampled_problems():
+    """C4 (256 head-dimension problems, d = 128, n = 131072 each) in the launch configuration
+    bench.py times: one workgroup walks all 1024 token tiles of a problem.  At d = 128 the
+    oracle can do whole problems, so sampled problems are compared in full."""
+    X, R, cfg = ktgen.make_problem("C4", seed=0, device="cuda")
+    b, n, d = X.shape
+    assert (b, n, d) == (256, 131072, 128)
+    ws = kt.Workspace()
+    rk = torch.empty((b, n), device="cuda")
+    dR = torch.empty((b, d, d), device="cuda")
+    loss = torch.empty(b, device="cuda")
+    kt.kt_kurtosis_loss_grad(X, R, loss=loss, row_kurt=rk, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    for p in (0, 101, 255):
+        o = oracle.loss_grad(ktgen.to_f64(X[p]), ktgen.to_f64(ktgen.bf16_round(R[p])))
+        assert abs(loss[p].item() - o["loss"]) <= 2e-2 * o["loss"], p
+        assert np.max(np.abs(rk[p].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= 2e-2, p
+        assert rel_fro(dR[p].cpu().numpy(), o["dR"]) <= 2e-2, p
+    # every problem: loss is the mean of its row values
+    means = rk.double().mean(1)
+    assert float(((loss.double() - means).abs() / means).max()) <= 1e-5

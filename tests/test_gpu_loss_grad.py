@@ -141,7 +141,9 @@ def test_c2_shape_chunk_vs_oracle_and_additivity():
 
 # ---- head-dimension problems (d = 128, bf16) take the single-pass fused kernel -------------------
 @pytest.mark.parametrize("n,batch,kt_", [(255, 1, 0.0), (256, 2, 0.0), (257, 1, 0.0), (3000, 5, 0.0),
-                                          (20000, 1, 0.0), (1500, 2, 2.6)])
+                                          (20000, 1, 0.0), (1500, 2, 2.6),
+                                          # several tiles per workgroup: all three X buffers in use
+                                          (1600, 64, 0.0), (1152, 128, 0.0), (2000, 40, 2.6)])
 def test_fused_d128_against_oracle(n, batch, kt_):
     X, R, cfg = ktgen.make_problem("C4", seed=n, n=n, batch=batch)
     if kt_ > 0:
