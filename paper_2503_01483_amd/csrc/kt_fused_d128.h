@@ -20,8 +20,11 @@
 // LDS (160 KiB): three X tiles and two G tiles of 32 KiB, rows of 256 bytes (X(i+2) arrives
 // while E reads X(i) and B reads X(i+1); stage E of one tile overlaps stages C-D of the next);
 // R^T lives in registers.
-//  X: 16-byte chunks XOR-swizzled with (row & 15) -> conflict-free fragment reads.
-//  G: 8-byte units XOR-swizzled with swz(t) = 4*(t%8) + (t/8)%4 -> conflict-free 8-byte
+//  X: 16-byte chunks XOR-swizzled with xkey(row) = 4*(row%4) + (row/4)%4: distinct over 16
+//  consecutive rows (conflict-free 16-byte fragment reads of 16 rows at one column), and the
+//  4 consecutive tokens a half wave reads transposed fall into 4 different 64-byte bank groups.
+//  G: 8-byte units XOR-swizzled with gkey(t) = 8*(t%4) + (t/4)%8: distinct over 32 tokens
+//  (conflict-free 8-byte stores from 32 token lanes), same property for the transposed reads.
 //  stores from 32 token lanes and conflict-free transposing reads.
 #pragma once
 #include "kt_aux.h"
@@ -35,6 +38,9 @@ constexpr int kF128GOff = 3 * kF128BufBytes;     // LDS: X[3] | G[2]
 constexpr int kF128LdsBytes = 5 * kF128BufBytes;  // 160 KiB
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int f128_xkey(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+__device__ __forceinline__ int f128_gkey(int t) { return ((t & 3) << 3) | ((t >> 2) & 7); }
 
 // Two transposing 8-byte LDS reads -> one MFMA operand (8 bf16 along K for this lane's row).
 // In a group of 16 lanes, lane r supplies the address of 4 consecutive features of token
@@ -125,12 +131,12 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
 
   // X tile movement: a wave owns rows 32*wave .. +31 of the tile and moves them with 8
   // instructions of 4 rows (1 KiB) each.  The 16-byte swizzle is applied on the source side:
-  // LDS chunk position (l & 15) of row r receives global chunk (l & 15) ^ (r & 15).
+  // LDS chunk position (l & 15) of row r receives global chunk (l & 15) ^ xkey(r).
   const int xrow0 = wave * 32 + (lane >> 4);  // tile row of instruction 0; instruction i: + 4 i
   const __bf16* xlane[4];                     // source of instruction i at tile 0: xlane[i & 3] + 4 i ldx
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    xlane[i] = X + (int64_t)xrow0 * ldx + (((lane & 15) ^ ((4 * i + (lane >> 4)) & 15)) << 3);
+    xlane[i] = X + (int64_t)xrow0 * ldx + (((lane & 15) ^ f128_xkey(4 * i + (lane >> 4))) << 3);
   auto load_tile = [&](int tile, int buf) __attribute__((always_inline)) {
     const unsigned dst = lds_base + buf * BUF + wave * (32 * 256);
     const int64_t tile_off = (int64_t)tile * T * ldx;
@@ -172,8 +178,8 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
   for (int ib = 0; ib < 2; ++ib) {
     const int u = (wm2 * 64 + ib * 32 + tr_feat) >> 2;  // 8-byte unit inside the X row
     const int sel = (u & 1) << 3, ch = u >> 1, t_hi = tr_tok + 4;
-    xa_lo[ib] = tr_tok * 256 + (((ch ^ (tr_tok & 15)) << 4) | sel);
-    xa_hi[ib] = t_hi * 256 + (((ch ^ (t_hi & 15)) << 4) | sel);
+    xa_lo[ib] = tr_tok * 256 + (((ch ^ f128_xkey(tr_tok)) << 4) | sel);
+    xa_hi[ib] = t_hi * 256 + (((ch ^ f128_xkey(t_hi)) << 4) | sel);
   }
 #pragma unroll
   for (int par = 0; par < 2; ++par)
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
     for (int jb = 0; jb < 2; ++jb) {
       const int u = (wn2 * 64 + jb * 32 + tr_feat) >> 2;
       const int t_lo = 16 * par + tr_tok, t_hi = t_lo + 4;
-      const int z_lo = ((t_lo & 7) << 2) | ((t_lo >> 3) & 3), z_hi = ((t_hi & 7) << 2) | ((t_hi >> 3) & 3);
+      const int z_lo = f128_gkey(t_lo), z_hi = f128_gkey(t_hi);
       gb_lo[par][jb] = tr_tok * 256 + ((u ^ z_lo) << 3);
       gb_hi[par][jb] = (tr_tok + 4) * 256 + ((u ^ z_hi) << 3);
     }
@@ -192,11 +198,11 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
   auto stage_b = [&](int buf) __attribute__((always_inline)) {
     const char* xrow = lds + buf * BUF + (wave * 32 + l32) * 256;
     intx4 xb[2];
-    xb[0] = *reinterpret_cast<const intx4*>(xrow + (((0 + half) ^ (l32 & 15)) << 4));
+    xb[0] = *reinterpret_cast<const intx4*>(xrow + (((0 + half) ^ f128_xkey(l32)) << 4));
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       if (s + 1 < 8)
-        xb[(s + 1) & 1] = *reinterpret_cast<const intx4*>(xrow + (((2 * (s + 1) + half) ^ (l32 & 15)) << 4));
+        xb[(s + 1) & 1] = *reinterpret_cast<const intx4*>(xrow + (((2 * (s + 1) + half) ^ f128_xkey(l32)) << 4));
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) {
         if (s == 0)
@@ -287,7 +293,7 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
       loss_acc += (half == 0 && valid) ? (double)term : 0.0;
       tick(integral_constant<int, 21>{});
       if (want_grad) {
-        const int swz = ((tok_local & 7) << 2) | ((tok_local >> 3) & 3);
+        const int swz = f128_gkey(tok_local);
         char* grow = lds + kF128GOff + gbuf_w * BUF + tok_local * 256;
         static_for<16>([&](auto g_c) __attribute__((always_inline)) {
           constexpr int g = decltype(g_c)::value, mb = g >> 2, q = g & 3;
