@@ -8,6 +8,7 @@
 
 #include "../../include/kt.h"
 #include "kt_aux.h"
+#include "kt_cayley_d128.h"
 #include "kt_fused_d128.h"
 
 namespace kt {
@@ -531,6 +532,20 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   const int D = (int)d;
   const int64_t dd = d * d;
   ProfScope prof(4, st);
+
+  if (d == 128) {  // whole retraction of a problem inside one workgroup (kt_cayley_d128.h)
+    static bool attr_done = false;
+    if (!attr_done) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(cayley_d128_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kC128LdsBytes) != hipSuccess)
+        return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(cayley_d128_kernel, dim3((unsigned)batch), dim3(256), kC128LdsBytes, st, R, dR,
+                       static_cast<__bf16*>(R_lowp), 0.5f * lr, ortho_err, info, kCayleyMaxIters, kCayleyTol);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley d=128 launch failed");
+    return KT_OK;
+  }
 
   if (p.split) {
     // three-term bf16 path: operands live as [d][3d] bf16

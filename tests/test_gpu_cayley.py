@@ -23,7 +23,7 @@ def _run(R, G, lr, want_lowp=True):
     return Rd.cpu(), None if lowp is None else lowp.cpu(), oe.cpu().numpy(), info.cpu().numpy()
 
 
-@pytest.mark.parametrize("d,batch,lr,gscale", [(128, 1, 1e-2, 1.0), (128, 3, 0.05, 1.0), (256, 1, 1e-2, 3.0),
+@pytest.mark.parametrize("d,batch,lr,gscale", [(128, 1, 1e-2, 1.0), (128, 3, 0.05, 1.0), (128, 40, 0.02, 2.0), (256, 1, 1e-2, 3.0),
                                                 (384, 2, 1e-3, 10.0), (512, 1, 1e-2, 1.0)])
 def test_against_oracle(d, batch, lr, gscale):
     g = torch.Generator().manual_seed(d + batch)
