@@ -19,7 +19,7 @@ def sources():
 
 def build_library(verbose=False):
     """Always recompiles (cross-compiles without a GPU). Returns the library path."""
-    extra = os.environ.get("KT_HIPCC_EXTRA", "").split()  # developer knob, e.g. -DKT_BIG_WGN=4
+    extra = os.environ.get("KT_HIPCC_EXTRA", "").split()  # developer knob: extra hipcc flags
     cmd = ["hipcc", *HIPCC_FLAGS, *extra, *sources(), "-o", LIB]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"

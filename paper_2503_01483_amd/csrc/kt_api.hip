@@ -49,10 +49,7 @@ struct ProfScope {
 
 // ------------------------------------------------------------------ tiles ---------
 using bf16 = __bf16;
-#ifndef KT_BIG_WGN
-#define KT_BIG_WGN 2
-#endif
-using TB_BIG = Tile<bf16, 256, 256, 2, KT_BIG_WGN>;   // d % 256 == 0
+using TB_BIG = Tile<bf16, 256, 256, 2, 2>;   // d % 256 == 0
 using TB_M128 = Tile<bf16, 128, 256, 1, 4>;  // features on m, d % 256 != 0
 using TB_N128 = Tile<bf16, 256, 128, 4, 1>;  // features on n, d % 256 != 0
 using TB_128 = Tile<bf16, 128, 128, 2, 2>;   // d x d outputs, d % 256 != 0

@@ -257,18 +257,14 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
       constexpr int s = g / NMMA, j = g % NMMA;
       using Buf = std::integral_constant<int, s & 1>;
       using NBuf = std::integral_constant<int, (s + 1) & 1>;
-#ifndef KT_EXP_NOBARRIER
       if constexpr (g == 3 * NMMA && MORE) lds_barrier();
-#endif
       mma(Buf{}, std::integral_constant<int, j>{});
       // fragments of the next sub-step: one LDS read behind each of the first slots
       static_for<NFRAG>([&](auto i_c) __attribute__((always_inline)) {
         constexpr int i = decltype(i_c)::value;
         if constexpr (i == j) {
-#ifndef KT_EXP_NOFREAD
           if constexpr (s < 3) fread(NBuf{}, i_c, Cur{}, std::integral_constant<int, (s + 1) & 3>{});
           else if constexpr (MORE) fread(NBuf{}, i_c, Nxt{}, C0{});
-#endif
         }
       });
       // next slab: registers -> other LDS stage, spread evenly over the three sub-steps
@@ -276,12 +272,8 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
       static_for<NLD>([&](auto i_c) __attribute__((always_inline)) {
         constexpr int i = decltype(i_c)::value;
         if constexpr (i * 3 * NMMA / NLD == g) {
-#ifndef KT_EXP_NOLSTORE
           if constexpr (MORE) lstore(i_c, Nxt{});
-#endif
-#ifndef KT_EXP_NOGLOAD
           if constexpr (LOAD2) gload(i_c);
-#endif
         }
       });
       __builtin_amdgcn_sched_barrier(0);
