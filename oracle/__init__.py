@@ -14,5 +14,6 @@ from .binding import (  # noqa: F401
     loss_grad,
     cayley_step,
     cayley_step_right,
+    cayley_adam_step,
     fakequant_int4,
 )

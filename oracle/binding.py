@@ -44,6 +44,9 @@ def _load():
     lib.kto_cayley_step.restype = ctypes.c_int
     lib.kto_cayley_step_right.argtypes = [dp, dp, i64, ctypes.c_double, dp]
     lib.kto_cayley_step_right.restype = ctypes.c_int
+    cd = ctypes.c_double
+    lib.kto_cayley_adam_step.argtypes = [dp, dp, dp, cd, i64, i64, cd, cd, cd, cd, cd, dp, dp, dp, dp]
+    lib.kto_cayley_adam_step.restype = ctypes.c_int
     lib.kto_fakequant_int4.argtypes = [dp, dp, i64, i64, ctypes.c_float, fp, fp, i8p, dp]
     lib.kto_fakequant_int4.restype = None
     _lib = lib
@@ -116,6 +119,22 @@ def cayley_step_right(R, G, lr):
     if rc != 0:
         raise ArithmeticError("singular system in Cayley step")
     return out
+
+
+def cayley_adam_step(R, G, M, v, k, lr, beta1=0.9, beta2=0.99, eps=1e-8, q=0.5):
+    """One Cayley Adam step.  Returns dict(R, M, v, r, alpha, w_norm)."""
+    R, G, M = _d(R), _d(G), _d(M)
+    d = R.shape[0]
+    Rout = np.empty((d, d), dtype=np.float64)
+    Mout = np.empty((d, d), dtype=np.float64)
+    vout = np.empty(1, dtype=np.float64)
+    scal = np.empty(3, dtype=np.float64)
+    rc = _load().kto_cayley_adam_step(_p(R), _p(G), _p(M), float(v), d, int(k), float(lr), float(beta1),
+                                      float(beta2), float(eps), float(q), _p(Rout), _p(Mout), _p(vout), _p(scal))
+    if rc != 0:
+        raise ArithmeticError("singular system in Cayley Adam step")
+    return {"R": Rout, "M": Mout, "v": float(vout[0]), "r": float(scal[0]), "alpha": float(scal[1]),
+            "w_norm": float(scal[2])}
 
 
 def fakequant_int4(X, R, clip=1.0, scales_in=None):

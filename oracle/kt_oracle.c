@@ -25,6 +25,13 @@
  *                                           manifold; exact solve by LU with
  *                                           partial pivoting)
  *   kto_cayley_step_right  the same retraction written on the right of R
+ *   kto_cayley_adam_step  one step of the Cayley Adam optimiser that the paper
+ *                                          names ("Learning the Rotations", Setup)
+ *                                          and defers to the cited work on Stiefel
+ *                                          optimisation for; the paper prints no
+ *                                          formula, so this follows that published
+ *                                          algorithm as this build reads it, with
+ *                                          the Cayley transform solved exactly
  *   kto_fakequant_int4  per-token symmetric 4-bit fake quantisation of X R
  *                                          (Background, "Uniform Quantization
  *                                           for k-bit Precision": b = 0,
@@ -254,6 +261,67 @@ int kto_cayley_step(const double *R, const double *G, int64_t d, double lr,
   const int rc = lu_solve(M, Rout, d, d);
   if (A_out) memcpy(A_out, A, sizeof(double) * dd);
   free(GRt); free(A); free(M); free(N);
+  return rc;
+}
+
+/*
+ * One step of Cayley Adam on the orthogonal group (square R), step counter k >= 1.
+ *   M1   = beta1 M + (1 - beta1) G                       first moment
+ *   v1   = beta2 v + (1 - beta2) ||G||_F^2               scalar second moment
+ *   r    = (1 - beta1^k) sqrt(v1 / (1 - beta2^k) + eps)  both bias corrections in one factor
+ *   What = M1 R^T - 1/2 R (R^T M1 R^T),  W = (What - What^T) / r     skew
+ *   M+   = r W R                                         momentum moved into the tangent space at R
+ *   a    = min(lr, 2 q / (||W||_F + eps))                keeps the fixed point of the transform contractive
+ *   R+   = (I + a/2 W)^-1 (I - a/2 W) R                  Cayley transform, solved exactly here
+ * Outputs: Rout, Mout (d*d), v_out, and scal_out[3] = {r, a, ||W||_F} (may be NULL).
+ * Returns 0, or -1 if the solve hit a zero pivot.
+ */
+int kto_cayley_adam_step(const double *R, const double *G, const double *M, double v,
+                         int64_t d, int64_t k, double lr, double beta1, double beta2,
+                         double eps, double q, double *Rout, double *Mout, double *v_out,
+                         double *scal_out) {
+  const size_t dd = (size_t)d * (size_t)d;
+  double *M1 = (double *)malloc(sizeof(double) * dd);
+  double *T1 = (double *)malloc(sizeof(double) * dd);
+  double *T2 = (double *)malloc(sizeof(double) * dd);
+  double *T3 = (double *)malloc(sizeof(double) * dd);
+  double *W = (double *)malloc(sizeof(double) * dd);
+  double *P = (double *)malloc(sizeof(double) * dd);
+  double *N = (double *)malloc(sizeof(double) * dd);
+  double g2 = 0.0;
+  for (size_t i = 0; i < dd; ++i) {
+    M1[i] = beta1 * M[i] + (1.0 - beta1) * G[i];
+    g2 += G[i] * G[i];
+  }
+  const double v1 = beta2 * v + (1.0 - beta2) * g2;
+  const double r = (1.0 - pow(beta1, (double)k)) * sqrt(v1 / (1.0 - pow(beta2, (double)k)) + eps);
+  mat_abt(M1, R, d, T1);  /* M1 R^T */
+  mat_atb(R, T1, d, T2);  /* R^T M1 R^T */
+  mat_ab(R, T2, d, T3);   /* R R^T M1 R^T */
+  for (size_t i = 0; i < dd; ++i) T1[i] -= 0.5 * T3[i]; /* What */
+  double w2 = 0.0;
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) {
+      const double w = (T1[i * d + j] - T1[j * d + i]) / r;
+      W[i * d + j] = w;
+      w2 += w * w;
+    }
+  const double wn = sqrt(w2);
+  mat_ab(W, R, d, Mout);
+  for (size_t i = 0; i < dd; ++i) Mout[i] *= r;
+  const double a1 = 2.0 * q / (wn + eps);
+  const double a = lr < a1 ? lr : a1;
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = 0; j < d; ++j) {
+      const double e = (i == j) ? 1.0 : 0.0;
+      P[i * d + j] = e + 0.5 * a * W[i * d + j];
+      N[i * d + j] = e - 0.5 * a * W[i * d + j];
+    }
+  mat_ab(N, R, d, Rout);
+  const int rc = lu_solve(P, Rout, d, d);
+  *v_out = v1;
+  if (scal_out) { scal_out[0] = r; scal_out[1] = a; scal_out[2] = wn; }
+  free(M1); free(T1); free(T2); free(T3); free(W); free(P); free(N);
   return rc;
 }
 
