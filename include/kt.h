@@ -123,6 +123,35 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * One Cayley Adam step on the orthogonal group: the optimiser the paper uses for all
+ * rotations ("Learning the Rotations"; Setup).  The paper prints no formula and defers to
+ * the cited work on optimisation over the Stiefel manifold; the step implemented here is
+ * that algorithm specialised to square orthogonal R, with the Cayley transform iterated to
+ * convergence instead of a fixed number of inner iterations (step counter k = `step` >= 1):
+ *
+ *   M  <- beta1 M + (1 - beta1) dR                      first moment
+ *   v  <- beta2 v + (1 - beta2) ||dR||_F^2              scalar second moment
+ *   r   = (1 - beta1^k) sqrt(v / (1 - beta2^k) + eps)
+ *   W   = (M R^T - R M^T) / (2 r)                       skew-symmetric
+ *   M  <- r W R                                         momentum moved into the tangent space at R
+ *   a   = min(lr, 2 q / (||W||_F + eps))                keeps the iteration below contractive
+ *   R+  = (I + a/2 W)^-1 (I - a/2 W) R                  fixed point Z <- R - (a/2) W (R + Z)
+ *
+ *  R        [batch][d][d] fp32, in/out.  d multiple of 128.
+ *  dR       [batch][d][d] fp32.
+ *  M        [batch][d][d] fp32 momentum, in/out (zeros before the first step).
+ *  v        [batch] fp32 second moment, in/out (1 before the first step).
+ *  R_lowp, ortho_err, info: as for kt_cayley_step.
+ *  scalars  [batch][3] fp32 {r, a, ||W||_F} of this step, or NULL.
+ *  Workspace: kt_workspace_bytes(KT_OP_CAYLEY, ...).  A zero gradient with zero momentum
+ *  gives W = 0 and leaves R unchanged.
+ */
+kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int64_t step,
+                              void* R_lowp, int64_t batch, int64_t d, float lr, float beta1,
+                              float beta2, float eps, float q, float* ortho_err, int32_t* info,
+                              float* scalars, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Rotate and fake-quantise to symmetric int4, one scale per token row
  * (Background, "Uniform Quantization for k-bit Precision" with k = 4, b = 0;
  * Setup: per-token dynamic symmetric quantisation; error as in Eq. 1):

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     kt_workspace_bytes,
     kt_kurtosis_loss_grad,
     kt_cayley_step,
+    kt_cayley_adam_step,
     kt_rotate_fakequant_int4,
     Workspace,
     kt_profile_enable,

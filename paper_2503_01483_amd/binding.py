@@ -12,7 +12,7 @@ KT_F32, KT_BF16 = 0, 1
 KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT = 0, 1, 2
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_cayley_step", "kt_rotate_fakequant_int4", "kt_profile_enable", "kt_profile_read",
+           "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_profile_enable", "kt_profile_read",
            "kt_profile_reset")
 
 
@@ -48,6 +48,9 @@ def lib():
                                         vp, vp, vp, vp, sz, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
+    L.kt_cayley_adam_step.restype = i32
+    L.kt_cayley_adam_step.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, f32, f32, f32, f32, f32, vp, vp, vp,
+                                      vp, sz, vp]
     L.kt_rotate_fakequant_int4.restype = i32
     L.kt_rotate_fakequant_int4.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32,
                                            vp, vp, vp, vp, vp, sz, vp]
@@ -147,6 +150,23 @@ def kt_cayley_step(R, dR, lr, *, R_lowp=None, ortho_err=None, info=None, workspa
     ws = (workspace or Workspace(R.device)).get(need)
     _check(lib().kt_cayley_step(_ptr(Rv), _ptr(dR), _ptr(R_lowp), batch, d, float(lr), _ptr(ortho_err),
                                 _ptr(info), _ptr(ws), ws.numel(), _stream(stream)))
+    return R
+
+
+def kt_cayley_adam_step(R, dR, M, v, step, lr, *, beta1=0.9, beta2=0.99, eps=1e-8, q=0.5, R_lowp=None,
+                        ortho_err=None, info=None, scalars=None, workspace=None, stream=None):
+    """In-place Cayley Adam step on R [batch][d][d] fp32 with state M [batch][d][d], v [batch]."""
+    Rv = R if R.dim() == 3 else R.unsqueeze(0)
+    batch, d, _ = Rv.shape
+    assert Rv.is_contiguous() and dR.is_contiguous() and M.is_contiguous() and v.is_contiguous()
+    assert dR.numel() == Rv.numel() and M.numel() == Rv.numel() and v.numel() == batch
+    assert R.dtype == dR.dtype == M.dtype == v.dtype == torch.float32
+    need = kt_workspace_bytes(KT_OP_CAYLEY, batch, 0, d, KT_F32)
+    ws = (workspace or Workspace(R.device)).get(need)
+    _check(lib().kt_cayley_adam_step(_ptr(Rv), _ptr(dR), _ptr(M), _ptr(v), int(step), _ptr(R_lowp), batch, d,
+                                     float(lr), float(beta1), float(beta2), float(eps), float(q),
+                                     _ptr(ortho_err), _ptr(info), _ptr(scalars), _ptr(ws), ws.numel(),
+                                     _stream(stream)))
     return R
 
 

@@ -191,7 +191,8 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
 
 struct CayleyPlan {
   bool split;  // three-term bf16 GEMMs on the bf16 matrix cores instead of fp32 MFMA
-  size_t o_m, o_b, o_rt, o_zt, o_u0, o_u1, o_delta, total;
+  size_t o_m, o_b, o_rt, o_zt, o_u0, o_u1, o_delta, o_g2, o_sq, o_scal, total;
+  int g2_blocks;  // Cayley Adam: block partials of ||G||^2 per problem
 };
 
 // Large problems run their d^3 GEMMs as three-term bf16 products (about 2^-17 relative
@@ -212,6 +213,11 @@ static CayleyPlan plan_cayley(int64_t batch, int64_t d) {
   p.o_u0 = c.take(p.split ? smat : mat);
   p.o_u1 = p.split ? c.take(smat) : p.o_m;
   p.o_delta = c.take((size_t)batch * kCayleyMaxIters * 4);
+  // Cayley Adam scalars: partial sums (fp64) and {r, alpha, ||W||, alpha/(2r)} per problem
+  p.g2_blocks = (int)(ceil_div(d * d / 4, 256) < 1024 ? ceil_div(d * d / 4, 256) : 1024);
+  p.o_g2 = c.take((size_t)batch * p.g2_blocks * 8);
+  p.o_sq = c.take((size_t)batch * (d / 32) * (d / 32) * 8);
+  p.o_scal = c.take((size_t)batch * 4 * 4);
   p.total = c.off;
   return p;
 }
@@ -506,20 +512,22 @@ kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64
                                               loss, row_kurt, dR, ws, st);
 }
 
-kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d, float lr,
-                         float* ortho_err, int32_t* info, void* workspace, size_t workspace_bytes,
-                         void* stream) {
-  g_err[0] = 0;
-  if (!R || !dR) return fail(KT_ERR_INVALID_ARG, "R and dR must not be null");
-  if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
-  if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
-  if (d > 32768 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range");
-  if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
-  const CayleyPlan p = plan_cayley(batch, d);
-  kt_status s = check_ws(workspace, workspace_bytes, p.total);
-  if (s != KT_OK) return s;
-  char* ws = static_cast<char*>(workspace);
-  hipStream_t st = static_cast<hipStream_t>(stream);
+// Optional Cayley Adam part of a retraction: moments already updated, r in scal[4b].
+struct AdamArgs {
+  float* M;            // [batch][d][d] momentum: in = beta1 M + (1-beta1) G, out = r W R
+  float lr, q, eps;
+  float* scal;         // [batch][4] device scalars {r, alpha, ||W||, alpha/(2r)}
+  double* sq_part;     // [batch][(d/32)^2] tile partials of ||S||^2
+  float* scalars_out;  // [batch][3] {r, alpha, ||W||} for the caller, or null
+};
+
+// Shared by the two optimisers.  P = G R^T, S = half_coef (P - P^T), then the Cayley transform
+// Z = (I + c S)^-1 (I - c S) R by the fixed point in transposed space (c = 1, or alpha/(2r) from
+// device memory for Adam), R <- Z.  For Adam, between set-up and iteration: step scalars, and
+// M <- S R (the momentum moved into the tangent space at R).
+static kt_status cayley_run(const CayleyPlan& p, char* ws, float* R, const float* G, void* R_lowp, int64_t batch,
+                            int64_t d, float half_coef, const AdamArgs* adam, float* ortho_err, int32_t* info,
+                            hipStream_t st) {
   float* Mm = reinterpret_cast<float*>(ws + p.o_m);
   float* Bm = reinterpret_cast<float*>(ws + p.o_b);
   float* Rt = reinterpret_cast<float*>(ws + p.o_rt);
@@ -528,21 +536,6 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   unsigned* delta = reinterpret_cast<unsigned*>(ws + p.o_delta);
   const int D = (int)d;
   const int64_t dd = d * d;
-  ProfScope prof(4, st);
-
-  if (d == 128) {  // whole retraction of a problem inside one workgroup (kt_cayley_d128.h)
-    static bool attr_done = false;
-    if (!attr_done) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(cayley_d128_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kC128LdsBytes) != hipSuccess)
-        return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
-      attr_done = true;
-    }
-    hipLaunchKernelGGL(cayley_d128_kernel, dim3((unsigned)batch), dim3(256), kC128LdsBytes, st, R, dR,
-                       static_cast<__bf16*>(R_lowp), 0.5f * lr, ortho_err, info, kCayleyMaxIters, kCayleyTol);
-    if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley d=128 launch failed");
-    return KT_OK;
-  }
 
   if (p.split) {
     // three-term bf16 path: operands live as [d][3d] bf16
@@ -551,16 +544,17 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
     const int64_t sd = 3 * d * d;
     const unsigned sb = (unsigned)(ceil_div(dd, 256) < 8192 ? ceil_div(dd, 256) : 8192);
     // M = dR R^T with dR as [hi|hi|lo] (in Us[0]) and R as [hi|lo|hi] (in Us[1])
-    hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, dR, D, D, Us[0], 0);
+    hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, G, D, D, Us[0], 0);
     hipLaunchKernelGGL(split3_kernel, dim3(sb, 1, (unsigned)batch), dim3(256), 0, st, R, D, D, Us[1], 1);
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "split launch failed");
     // below d = 4096 a 256 x 256 tiling leaves most CUs without a tile: use 128 x 128 there
     const bool big = (d / 256) * (d / 256) * batch >= kNumCUs;
-    auto product = [&](const __bf16* A3, const __bf16* B3, int it) -> bool {
+    auto product = [&](const __bf16* A3, const __bf16* B3, int it, float* Cdst = nullptr, float alpha = 1.f) -> bool {
       auto go = [&](auto tile_tag) -> bool {
         using TL = decltype(tile_tag);
         EpiCayleyProduct<TL> e;
-        e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
+        e.C = Cdst ? Cdst : Mm; e.alpha = alpha;
+        e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
         e.delta = delta; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
         return launch_gemm<TL>(A3, 3 * d, sd, D, B3, 3 * d, sd, D, 3 * d, 0, (int)batch, e, st);
       };
@@ -569,13 +563,21 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
     if (!product(Us[0], Us[1], 0)) return fail(KT_ERR_DEVICE, "dR R^T GEMM launch failed");
     hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, delta, batch * kCayleyMaxIters, 0u);
     hipLaunchKernelGGL(cayley_setup_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Mm, R,
-                       D, 0.5f * lr, (float*)nullptr, Rt, Zt, (float*)nullptr, Bs, Us[0]);
+                       D, half_coef, (float*)nullptr, Rt, Zt, (float*)nullptr, Bs, Us[0], adam ? adam->sq_part : nullptr);
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley set-up launch failed");
+    if (adam) {
+      hipLaunchKernelGGL(adam_scalars2_kernel, dim3((unsigned)batch), dim3(256), 0, st, adam->sq_part,
+                         (int)((d / 32) * (d / 32)), adam->lr, adam->q, adam->eps, adam->scal, adam->scalars_out);
+      if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley Adam scalar launch failed");
+      // M <- S R = (1/2) S (2 Rt)^T: S sits in Bs as [hi|lo|hi], 2 Rt in Us[0] as [hi|hi|lo]; the same three
+      // cross terms come out whichever operand carries which layout
+      if (!product(Bs, Us[0], 0, adam->M, 0.5f)) return fail(KT_ERR_DEVICE, "momentum projection GEMM launch failed");
+    }
     const unsigned ub = (unsigned)(ceil_div(dd / 4, 256) < 2048 ? ceil_div(dd / 4, 256) : 2048);
     for (int it = 0; it < kCayleyMaxIters; ++it) {
       if (!product(Us[it & 1], Bs, it)) return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
       hipLaunchKernelGGL(cayley_update_kernel, dim3(ub, (unsigned)batch), dim3(256), 0, st, Mm, Rt, Zt,
-                         Us[(it + 1) & 1], D, delta, it, kCayleyMaxIters, kCayleyTol);
+                         Us[(it + 1) & 1], D, delta, it, kCayleyMaxIters, kCayleyTol, adam ? adam->scal : nullptr);
       if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley update launch failed");
     }
   } else {
@@ -583,20 +585,30 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   {
     EpiStore<TF> e;
     e.C = Mm; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
-    if (!launch_gemm<TF>(dR, d, dd, D, R, d, dd, D, d, 0, (int)batch, e, st))
+    if (!launch_gemm<TF>(G, d, dd, D, R, d, dd, D, d, 0, (int)batch, e, st))
       return fail(KT_ERR_DEVICE, "dR R^T GEMM launch failed");
   }
   // delta[it] collects max |Zt_new - Zt_old| of iteration it through atomicMax
   hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, delta, batch * kCayleyMaxIters, 0u);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "fill launch failed");
   hipLaunchKernelGGL(cayley_setup_kernel, dim3(D / 32, D / 32, (unsigned)batch), dim3(256), 0, st, Mm, R,
-                     D, 0.5f * lr, Bm, Rt, Zt, U[0], (__bf16*)nullptr, (__bf16*)nullptr);
+                     D, half_coef, Bm, Rt, Zt, U[0], (__bf16*)nullptr, (__bf16*)nullptr, adam ? adam->sq_part : nullptr);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley set-up launch failed");
+  if (adam) {
+    hipLaunchKernelGGL(adam_scalars2_kernel, dim3((unsigned)batch), dim3(256), 0, st, adam->sq_part,
+                 (int)((d / 32) * (d / 32)), adam->lr, adam->q, adam->eps, adam->scal, adam->scalars_out);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley Adam scalar launch failed");
+    EpiStore<TF> e;  // M <- S R = S (Rt)^T
+    e.C = adam->M; e.ldc = d; e.batch_stride = dd; e.split_stride = 0; e.M = D; e.N = D;
+    if (!launch_gemm<TF>(Bm, d, dd, D, Rt, d, dd, D, d, 0, (int)batch, e, st))
+      return fail(KT_ERR_DEVICE, "momentum projection GEMM launch failed");
+  }
   // fixed point in transposed space: Zt <- Rt - U Bm^T, U <- Rt + Zt
   for (int it = 0; it < kCayleyMaxIters; ++it) {
     EpiCayleyIter<TF> e;
     e.Rt = Rt; e.Zt = Zt; e.Unew = U[(it + 1) & 1]; e.Usplit = nullptr; e.delta = delta;
     e.d = D; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
+    e.bscale = adam ? adam->scal : nullptr;
     if (!launch_gemm<TF>(U[it & 1], d, dd, D, Bm, d, dd, D, d, 0, (int)batch, e, st))
       return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
   }
@@ -618,6 +630,74 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "orthogonality diagonal launch failed");
   }
   return KT_OK;
+}
+
+
+kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d, float lr,
+                         float* ortho_err, int32_t* info, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  g_err[0] = 0;
+  if (!R || !dR) return fail(KT_ERR_INVALID_ARG, "R and dR must not be null");
+  if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
+  if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
+  if (d > 32768 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range");
+  if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
+  const CayleyPlan p = plan_cayley(batch, d);
+  kt_status s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope prof(4, st);
+  if (d == 128) {  // whole retraction of a problem inside one workgroup (kt_cayley_d128.h)
+    static bool attr_done = false;
+    if (!attr_done) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(cayley_d128_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kC128LdsBytes) != hipSuccess)
+        return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(cayley_d128_kernel, dim3((unsigned)batch), dim3(256), kC128LdsBytes, st, R, dR,
+                       static_cast<__bf16*>(R_lowp), 0.5f * lr, ortho_err, info, kCayleyMaxIters, kCayleyTol);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley d=128 launch failed");
+    return KT_OK;
+  }
+
+  return cayley_run(p, ws, R, dR, R_lowp, batch, d, 0.5f * lr, nullptr, ortho_err, info, st);
+}
+
+kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int64_t step, void* R_lowp,
+                              int64_t batch, int64_t d, float lr, float beta1, float beta2, float eps, float q,
+                              float* ortho_err, int32_t* info, float* scalars, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!R || !dR || !M || !v) return fail(KT_ERR_INVALID_ARG, "R, dR, M and v must not be null");
+  if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
+  if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
+  if (d > 32768 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range");
+  if (step < 1) return fail(KT_ERR_INVALID_ARG, "step counts from 1");
+  if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+    return fail(KT_ERR_INVALID_ARG, "beta1 and beta2 must lie in [0, 1)");
+  if (!(eps >= 0.f) || !(q > 0.f)) return fail(KT_ERR_INVALID_ARG, "eps must be >= 0 and q > 0");
+  const CayleyPlan p = plan_cayley(batch, d);
+  kt_status s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope prof(4, st);
+  AdamArgs a;
+  a.M = M; a.lr = lr; a.q = q; a.eps = eps; a.scalars_out = scalars;
+  a.scal = reinterpret_cast<float*>(ws + p.o_scal);
+  a.sq_part = reinterpret_cast<double*>(ws + p.o_sq);
+  double* g2_part = reinterpret_cast<double*>(ws + p.o_g2);
+  hipLaunchKernelGGL(adam_moment_kernel, dim3((unsigned)p.g2_blocks, (unsigned)batch), dim3(256), 0, st, M, dR,
+                     d * d, beta1, g2_part);
+  const double c1 = 1.0 - pow((double)beta1, (double)step), c2 = 1.0 - pow((double)beta2, (double)step);
+  hipLaunchKernelGGL(adam_scalars1_kernel, dim3((unsigned)batch), dim3(256), 0, st, g2_part, p.g2_blocks, v, beta2,
+                     c1, c2, eps, a.scal);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley Adam moment launch failed");
+  // P = M1 R^T, S = (P - P^T)/2 (= r W for orthogonal R), then the transform with c = alpha/(2r)
+  return cayley_run(p, ws, R, M, R_lowp, batch, d, 0.5f, &a, ortho_err, info, st);
 }
 
 kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, int64_t ldr,

@@ -234,9 +234,12 @@ __global__ __launch_bounds__(256) void cayley_setup_kernel(const float* __restri
                                                            float* __restrict__ Zt,
                                                            float* __restrict__ U0,
                                                            __bf16* __restrict__ Bs,
-                                                           __bf16* __restrict__ Us) {
+                                                           __bf16* __restrict__ Us,
+                                                           double* __restrict__ sq_part) {
   __shared__ float tm[32][33];
   __shared__ float tr[32][33];
+  __shared__ double shsum[256];
+  double sq = 0.0;
   const int64_t bo = (int64_t)blockIdx.z * d * d;
   const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
@@ -255,6 +258,7 @@ __global__ __launch_bounds__(256) void cayley_setup_kernel(const float* __restri
     const float m_ij = Mm[idx];
     const float m_ji = tm[tx][rr];
     const float b = half_lr * (m_ij - m_ji);
+    sq += (double)b * (double)b;
     const float rt = tr[tx][rr];  // R[j0+tx][i0+rr] = Rt[i0+rr][j0+tx]
     Rt[idx] = rt;
     Zt[idx] = rt;
@@ -270,6 +274,76 @@ __global__ __launch_bounds__(256) void cayley_setup_kernel(const float* __restri
       U0[idx] = 2.f * rt;
     }
   }
+  if (sq_part) {  // per-tile sum of Bm^2 (uniform branch), added up in fixed order by the caller's kernel
+    const double tot = block_sum_256(sq, shsum);
+    if (threadIdx.x == 0)
+      sq_part[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x] = tot;
+  }
+}
+
+// ---- Cayley Adam: moments and step scalars (the optimiser the paper names; the update rule is
+// that of the cited work on Stiefel-manifold optimisation) --------------------------------------
+// M <- beta1 M + (1 - beta1) G in place; g2_part[batch][gridDim.x] = block partial sums of G^2.
+__global__ __launch_bounds__(256) void adam_moment_kernel(float* __restrict__ M, const float* __restrict__ G,
+                                                          int64_t dd, float beta1,
+                                                          double* __restrict__ g2_part) {
+  __shared__ double sh[256];
+  const int64_t bo = (int64_t)blockIdx.y * dd;
+  double s = 0.0;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < dd / 4; q += (int64_t)gridDim.x * 256) {
+    const floatx4 g = *reinterpret_cast<const floatx4*>(G + bo + 4 * q);
+    floatx4 m = *reinterpret_cast<const floatx4*>(M + bo + 4 * q);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      m[e] = beta1 * m[e] + (1.f - beta1) * g[e];
+      s += (double)g[e] * (double)g[e];
+    }
+    *reinterpret_cast<floatx4*>(M + bo + 4 * q) = m;
+  }
+  const double tot = block_sum_256(s, sh);
+  if (threadIdx.x == 0) g2_part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
+}
+
+// v <- beta2 v + (1 - beta2) ||G||_F^2;  scal[4b] = r = c1 sqrt(v / c2 + eps) with the bias
+// corrections c1 = 1 - beta1^k, c2 = 1 - beta2^k taken by the host in double.  grid = batch.
+__global__ __launch_bounds__(256) void adam_scalars1_kernel(const double* __restrict__ g2_part, int nblk,
+                                                            float* __restrict__ v, float beta2, double c1,
+                                                            double c2, float eps, float* __restrict__ scal) {
+  __shared__ double sh[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nblk; i += 256) s += g2_part[(int64_t)blockIdx.x * nblk + i];
+  const double g2 = block_sum_256(s, sh);
+  if (threadIdx.x == 0) {
+    const double v1 = (double)beta2 * (double)v[blockIdx.x] + (1.0 - (double)beta2) * g2;
+    v[blockIdx.x] = (float)v1;
+    scal[4 * blockIdx.x] = (float)(c1 * sqrt(v1 / c2 + (double)eps));
+  }
+}
+
+// From the tile partials of ||S||_F^2 (S = (P - P^T)/2, W = S / r):
+// scal[4b+1] = alpha = min(lr, 2 q / (||W|| + eps)), [4b+2] = ||W||_F, [4b+3] = alpha / (2 r), the factor of S
+// in the fixed point Y = X - (alpha/2) W (X + Y).  grid = batch.
+__global__ __launch_bounds__(256) void adam_scalars2_kernel(const double* __restrict__ sq_part, int ntile,
+                                                            float lr, float q, float eps,
+                                                            float* __restrict__ scal,
+                                                            float* __restrict__ scalars_out) {
+  __shared__ double sh[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < ntile; i += 256) s += sq_part[(int64_t)blockIdx.x * ntile + i];
+  const double s2 = block_sum_256(s, sh);
+  if (threadIdx.x == 0) {
+    const float r = scal[4 * blockIdx.x];
+    const float wn = (float)(sqrt(s2) / (double)r);
+    const float alpha = fminf(lr, 2.f * q / (wn + eps));
+    scal[4 * blockIdx.x + 1] = alpha;
+    scal[4 * blockIdx.x + 2] = wn;
+    scal[4 * blockIdx.x + 3] = alpha / (2.f * r);
+    if (scalars_out) {
+      scalars_out[3 * blockIdx.x] = r;
+      scalars_out[3 * blockIdx.x + 1] = alpha;
+      scalars_out[3 * blockIdx.x + 2] = wn;
+    }
+  }
 }
 
 // One fixed-point update from the GEMM product C = U B^T (three-term bf16 path):
@@ -281,7 +355,8 @@ __global__ __launch_bounds__(256) void cayley_update_kernel(const float* __restr
                                                             float* __restrict__ Zt,
                                                             __bf16* __restrict__ Us, int d,
                                                             unsigned* __restrict__ delta, int it,
-                                                            int max_iters, float tol) {
+                                                            int max_iters, float tol,
+                                                            const float* __restrict__ bscale) {
   __shared__ unsigned sh[4];
   unsigned* dl = delta + (int64_t)blockIdx.y * max_iters;
   if (it > 0 && cayley_converged(dl, it - 1, tol)) {
@@ -289,6 +364,7 @@ __global__ __launch_bounds__(256) void cayley_update_kernel(const float* __restr
     return;
   }
   const int64_t dd = (int64_t)d * d, bo = (int64_t)blockIdx.y * dd;
+  const float bs = bscale ? bscale[4 * blockIdx.y + 3] : 1.f;  // Cayley Adam: factor of S
   unsigned dmax = 0u;
   for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < dd / 4; q += (int64_t)gridDim.x * 256) {
     const int64_t i = q * 4;
@@ -300,7 +376,7 @@ __global__ __launch_bounds__(256) void cayley_update_kernel(const float* __restr
     __bf16 hi[4], lo[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      z[e] = rt[e] - c[e];
+      z[e] = rt[e] - bs * c[e];
       dmax = umax(dmax, abs_bits(z[e] - zo[e]));
       split_bf16(rt[e] + z[e], hi[e], lo[e]);
     }

@@ -134,6 +134,7 @@ struct EpiStore : EpiBase {
   float* C;
   int64_t ldc, batch_stride, split_stride;
   int M, N;
+  float alpha = 1.f;  // C = alpha * acc
   __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
                                              int, int ks, int m0, int n0) const {
     const Frag<TL> f;
@@ -146,7 +147,7 @@ struct EpiStore : EpiBase {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int m = m0 + f.m_of(mb, r);
-          if (m < M && n < N) base[(int64_t)m * ldc + n] = acc[mb][nb][r];
+          if (m < M && n < N) base[(int64_t)m * ldc + n] = alpha * acc[mb][nb][r];
         }
       }
   }
@@ -190,6 +191,7 @@ struct EpiCayleyIter {
   unsigned* delta;  // [batch][max_iters]
   int d, it, max_iters;
   float tol;
+  const float* bscale = nullptr;  // acc is scaled by bscale[4 * batch + 3] when given (Cayley Adam)
   __device__ __forceinline__ bool skip(int batch) const {
     if (it == 0) return false;
     const unsigned* dl = delta + (int64_t)batch * max_iters;
@@ -202,6 +204,7 @@ struct EpiCayleyIter {
                                              int, int, int m0, int n0) const {
     const Frag<TL> f;
     const int64_t bo = (int64_t)batch * d * d;
+    const float bs = bscale ? bscale[4 * batch + 3] : 1.f;
     unsigned dmax = 0u;
 #pragma unroll
     for (int mb = 0; mb < TL::MB; ++mb)
@@ -214,7 +217,7 @@ struct EpiCayleyIter {
           if (m < d && n < d) {
             const int64_t idx = bo + (int64_t)m * d + n;
             const float rt = Rt[idx];
-            const float z = rt - acc[mb][nb][r];
+            const float z = rt - bs * acc[mb][nb][r];
             dmax = umax(dmax, abs_bits(z - Zt[idx]));
             Zt[idx] = z;
             const float u = rt + z;

@@ -67,6 +67,15 @@ def test_argument_errors_are_synchronous():
     assert st == 1
     st = L.kt_cayley_step(fake, fake, None, 1, 64, 0.01, None, None, ws, 1 << 30, None)
     assert st == 2
+    st = L.kt_cayley_adam_step(fake, fake, None, fake, 1, None, 1, 128, 0.01, 0.9, 0.99, 1e-8, 0.5, None, None, None,
+                               ws, 1 << 30, None)
+    assert st == 1 and "null" in kt.kt_last_error()
+    st = L.kt_cayley_adam_step(fake, fake, fake, fake, 0, None, 1, 128, 0.01, 0.9, 0.99, 1e-8, 0.5, None, None, None,
+                               ws, 1 << 30, None)
+    assert st == 1 and "step" in kt.kt_last_error()
+    st = L.kt_cayley_adam_step(fake, fake, fake, fake, 1, None, 1, 128, 0.01, 1.0, 0.99, 1e-8, 0.5, None, None, None,
+                               ws, 1 << 30, None)
+    assert st == 1 and "beta" in kt.kt_last_error()
     st = L.kt_cayley_step(fake, fake, None, 1, 128, float("nan"), None, None, ws, 1 << 30, None)
     assert st == 1
     st = L.kt_rotate_fakequant_int4(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.5, None, fake, None, None, ws, 1 << 30, None)
