@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
+    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
+                    help="retraction timed inside the step: Cayley SGD (default, the headline step) or Cayley Adam")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after timing, copy X once with a plain device copy (a kernel of known traffic, "
                          "2 x bytes(X), against which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled)")
@@ -70,10 +72,19 @@ def main():
     dR = torch.empty((batch, d, d), device=dev)
     info = torch.zeros(batch, dtype=torch.int32, device=dev)
     Rw = R.clone()
+    adam = args.optimizer == "adam"
+    Mom = torch.zeros_like(dR) if adam else None
+    vmom = torch.ones(batch, device=dev) if adam else None
+    counter = [0]
 
     def step():
         kt.kt_kurtosis_loss_grad(X, Rw, loss=loss, dR=dR, workspace=ws)
-        if not args.no_cayley:
+        if args.no_cayley:
+            return
+        if adam:
+            counter[0] += 1
+            kt.kt_cayley_adam_step(Rw, dR, Mom, vmom, counter[0], lr, info=info, workspace=ws)
+        else:
             kt.kt_cayley_step(Rw, dR, lr, info=info, workspace=ws)
 
     for _ in range(args.warmup):
@@ -158,7 +169,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: n={n} tokens x d={d}, batch={batch}, "
-                               f"loss+grad{'' if args.no_cayley else '+Cayley'} step, lr={lr}",
+                               f"loss+grad{'' if args.no_cayley else ('+Cayley Adam' if adam else '+Cayley')} step, lr={lr}",
                    "global_batch": batch * n, "hidden": d},
         "tflops_algorithmic_4nd2": round(alg_tflops, 2),
         "tflops_hardware_6nd2": None if fused else round(hw_tflops, 2),

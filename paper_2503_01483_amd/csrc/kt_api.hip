@@ -462,54 +462,21 @@ static kt_status run_quant(const QuantPlan& p, const void* X, int64_t ldx, const
 using namespace kt;
 
 // =================================================================== C ABI =========
-extern "C" {
-
-int32_t kt_version(void) { return 100; }
-
-const char* kt_last_error(void) { return g_err; }
-
-size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype) {
-  if (batch < 1 || d < 1 || d % 128 != 0) return 0;
-  if (x_dtype != KT_F32 && x_dtype != KT_BF16) return 0;
-  switch (op) {
-    case KT_OP_LOSS_GRAD:
-      if (n < 1) return 0;
-      return plan_loss_grad(batch, n, d, x_dtype).total;
-    case KT_OP_CAYLEY:
-      return plan_cayley(batch, d).total;
-    case KT_OP_FAKEQUANT:
-      if (n < 1) return 0;
-      return plan_quant(batch, n, d, x_dtype).total;
-    default:
-      return 0;
+// d = 128: one workgroup per problem does the whole step (kt_cayley_d128.h).
+template <bool ADAM>
+static kt_status launch_cayley_d128(float* R, const float* G, void* R_lowp, int64_t batch, float half_coef,
+                                    float* ortho_err, int32_t* info, const C128Adam& ad, hipStream_t st) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(cayley_d128_kernel<ADAM>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kC128LdsBytes) != hipSuccess)
+      return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
+    attr_done = true;
   }
-}
-
-kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
-                                int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype,
-                                kt_dtype r_dtype, float kappa_target, float* loss, float* row_kurt,
-                                float* dR, void* workspace, size_t workspace_bytes, void* stream) {
-  g_err[0] = 0;
-  kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
-  if (s != KT_OK) return s;
-  if (!loss) return fail(KT_ERR_INVALID_ARG, "loss must not be null");
-  if (!(kappa_target >= 0.f)) return fail(KT_ERR_INVALID_ARG, "kappa_target must be >= 0");
-  const LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype);
-  s = check_ws(workspace, workspace_bytes, p.total);
-  if (s != KT_OK) return s;
-  char* ws = static_cast<char*>(workspace);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (p.fused)
-    return run_loss_grad_fused(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss, row_kurt, dR,
-                               ws, st);
-  if (p.fp32)
-    return run_loss_grad<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss,
-                                        row_kurt, dR, ws, st);
-  if (d % 256 == 0)
-    return run_loss_grad<bf16, TB_BIG, TB_BIG>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
-                                               loss, row_kurt, dR, ws, st);
-  return run_loss_grad<bf16, TB_M128, TB_128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
-                                              loss, row_kurt, dR, ws, st);
+  hipLaunchKernelGGL(cayley_d128_kernel<ADAM>, dim3((unsigned)batch), dim3(256), kC128LdsBytes, st, R, G,
+                     static_cast<__bf16*>(R_lowp), half_coef, ortho_err, info, kCayleyMaxIters, kCayleyTol, ad);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley d=128 launch failed");
+  return KT_OK;
 }
 
 // Optional Cayley Adam part of a retraction: moments already updated, r in scal[4b].
@@ -633,6 +600,56 @@ static kt_status cayley_run(const CayleyPlan& p, char* ws, float* R, const float
 }
 
 
+extern "C" {
+
+int32_t kt_version(void) { return 100; }
+
+const char* kt_last_error(void) { return g_err; }
+
+size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype) {
+  if (batch < 1 || d < 1 || d % 128 != 0) return 0;
+  if (x_dtype != KT_F32 && x_dtype != KT_BF16) return 0;
+  switch (op) {
+    case KT_OP_LOSS_GRAD:
+      if (n < 1) return 0;
+      return plan_loss_grad(batch, n, d, x_dtype).total;
+    case KT_OP_CAYLEY:
+      return plan_cayley(batch, d).total;
+    case KT_OP_FAKEQUANT:
+      if (n < 1) return 0;
+      return plan_quant(batch, n, d, x_dtype).total;
+    default:
+      return 0;
+  }
+}
+
+kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype,
+                                kt_dtype r_dtype, float kappa_target, float* loss, float* row_kurt,
+                                float* dR, void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
+  if (s != KT_OK) return s;
+  if (!loss) return fail(KT_ERR_INVALID_ARG, "loss must not be null");
+  if (!(kappa_target >= 0.f)) return fail(KT_ERR_INVALID_ARG, "kappa_target must be >= 0");
+  const LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype);
+  s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p.fused)
+    return run_loss_grad_fused(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss, row_kurt, dR,
+                               ws, st);
+  if (p.fp32)
+    return run_loss_grad<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss,
+                                        row_kurt, dR, ws, st);
+  if (d % 256 == 0)
+    return run_loss_grad<bf16, TB_BIG, TB_BIG>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
+                                               loss, row_kurt, dR, ws, st);
+  return run_loss_grad<bf16, TB_M128, TB_128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
+                                              loss, row_kurt, dR, ws, st);
+}
+
 kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d, float lr,
                          float* ortho_err, int32_t* info, void* workspace, size_t workspace_bytes,
                          void* stream) {
@@ -648,20 +665,8 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   ProfScope prof(4, st);
-  if (d == 128) {  // whole retraction of a problem inside one workgroup (kt_cayley_d128.h)
-    static bool attr_done = false;
-    if (!attr_done) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(cayley_d128_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kC128LdsBytes) != hipSuccess)
-        return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
-      attr_done = true;
-    }
-    hipLaunchKernelGGL(cayley_d128_kernel, dim3((unsigned)batch), dim3(256), kC128LdsBytes, st, R, dR,
-                       static_cast<__bf16*>(R_lowp), 0.5f * lr, ortho_err, info, kCayleyMaxIters, kCayleyTol);
-    if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley d=128 launch failed");
-    return KT_OK;
-  }
-
+  if (d == 128)  // whole retraction of a problem inside one workgroup (kt_cayley_d128.h)
+    return launch_cayley_d128<false>(R, dR, R_lowp, batch, 0.5f * lr, ortho_err, info, C128Adam{}, st);
   return cayley_run(p, ws, R, dR, R_lowp, batch, d, 0.5f * lr, nullptr, ortho_err, info, st);
 }
 
@@ -685,6 +690,13 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   ProfScope prof(4, st);
+  const double c1 = 1.0 - pow((double)beta1, (double)step), c2 = 1.0 - pow((double)beta2, (double)step);
+  if (d == 128) {
+    C128Adam ad;
+    ad.M = M; ad.v = v; ad.scalars_out = scalars; ad.lr = lr; ad.beta1 = beta1; ad.beta2 = beta2;
+    ad.eps = eps; ad.q = q; ad.c1 = c1; ad.c2 = c2;
+    return launch_cayley_d128<true>(R, dR, R_lowp, batch, 0.5f, ortho_err, info, ad, st);
+  }
   AdamArgs a;
   a.M = M; a.lr = lr; a.q = q; a.eps = eps; a.scalars_out = scalars;
   a.scal = reinterpret_cast<float*>(ws + p.o_scal);
@@ -692,7 +704,6 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
   double* g2_part = reinterpret_cast<double*>(ws + p.o_g2);
   hipLaunchKernelGGL(adam_moment_kernel, dim3((unsigned)p.g2_blocks, (unsigned)batch), dim3(256), 0, st, M, dR,
                      d * d, beta1, g2_part);
-  const double c1 = 1.0 - pow((double)beta1, (double)step), c2 = 1.0 - pow((double)beta2, (double)step);
   hipLaunchKernelGGL(adam_scalars1_kernel, dim3((unsigned)batch), dim3(256), 0, st, g2_part, p.g2_blocks, v, beta2,
                      c1, c2, eps, a.scal);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley Adam moment launch failed");

@@ -6,9 +6,10 @@
 // and R^T / the iterate in registers, and runs
 //   M = dR R^T,  B = (lr/2)(M - M^T),  Zt <- Rt - U B^T,  U <- Rt + Zt  (to convergence),
 //   R <- Zt^T,   max |R^T R - I|
-// without touching HBM in between.  Same arithmetic (fp32 MFMA, transposed-space fixed point of the
-// Cayley SGD update the paper names in its implementation details), same convergence rule and
-// same outputs as the generic fp32 path.
+// without touching HBM in between.  The Cayley Adam variant (ADAM = true) adds, in the same
+// launch, the moment updates, the step scalars and the momentum projection M <- S R.
+// Same arithmetic (fp32 MFMA, transposed-space fixed point of the Cayley updates the paper names
+// in its implementation details), same convergence rule and same outputs as the generic fp32 path.
 //
 // LDS matrices are [128 rows][128 floats], 16-byte chunks XOR-swizzled with (row & 15) so that the
 // 16-byte fragment reads of 16 consecutive rows at one K position are conflict-free.
@@ -19,7 +20,7 @@
 namespace kt {
 
 constexpr int kC128MatBytes = 128 * 128 * 4;
-constexpr int kC128LdsBytes = 2 * kC128MatBytes + 64;
+constexpr int kC128LdsBytes = 2 * kC128MatBytes + 64 + 256 * 8;  // + max slots + fp64 sum scratch
 
 __device__ __forceinline__ int c128_addr(int row, int col) {
   return row * 512 + ((((col >> 2) ^ (row & 15))) << 4) + ((col & 3) << 2);
@@ -61,36 +62,70 @@ __device__ __forceinline__ unsigned c128_block_umax(unsigned v, unsigned* red, i
   return umax(umax(red[0], red[1]), umax(red[2], red[3]));
 }
 
+// Hyper-parameters of the Adam variant; c1 = 1 - beta1^k, c2 = 1 - beta2^k from the host.
+struct C128Adam {
+  float* M;            // [batch][128][128] momentum, in/out
+  float* v;            // [batch] second moment, in/out
+  float* scalars_out;  // [batch][3] {r, alpha, ||W||_F} or null
+  float lr, beta1, beta2, eps, q;
+  double c1, c2;
+};
+
 // grid = batch, 256 threads, kC128LdsBytes of dynamic LDS.
+// SGD: S = half_lr (P - P^T) with P = dR R^T, transform factor 1.
+// Adam: S = (P - P^T)/2 with P = M1 R^T, transform factor alpha/(2r), M <- S R.
+template <bool ADAM>
 __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R, const float* __restrict__ dR,
                                                           __bf16* __restrict__ R_lowp, float half_lr,
                                                           float* __restrict__ ortho_err,
-                                                          int32_t* __restrict__ info, int max_iters, float tol) {
+                                                          int32_t* __restrict__ info, int max_iters, float tol,
+                                                          C128Adam ad) {
   extern __shared__ __align__(16) char lds[];
   char* bufA = lds;
   char* bufB = lds + kC128MatBytes;
   unsigned* red = reinterpret_cast<unsigned*>(lds + 2 * kC128MatBytes);
+  double* dsum = reinterpret_cast<double*>(lds + 2 * kC128MatBytes + 64);
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int half = lane >> 5, l32 = lane & 31, wm = wave >> 1, wn = wave & 1;
+  const int half = lane >> 5, l32 = lane & 31, wm = wave >> 1, wn2 = wave & 1;
   float* Rb = R + (int64_t)b * 16384;
   const float* Gb = dR + (int64_t)b * 16384;
 
-  // dR -> bufA, R -> bufB
+  // dR (Adam: M1 = beta1 M + (1 - beta1) dR) -> bufA, R -> bufB
+  float* Mb = ADAM ? ad.M + (int64_t)b * 16384 : nullptr;
+  double g2 = 0.0;
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
     const int f = i * 256 + tid, row = f >> 5, ch = f & 31;
     const int off = row * 512 + ((ch ^ (row & 15)) << 4);
-    *reinterpret_cast<intx4*>(bufA + off) = *reinterpret_cast<const intx4*>(Gb + row * 128 + ch * 4);
+    floatx4 g = *reinterpret_cast<const floatx4*>(Gb + row * 128 + ch * 4);
+    if constexpr (ADAM) {
+      const floatx4 m = *reinterpret_cast<const floatx4*>(Mb + row * 128 + ch * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        g2 += (double)g[e] * (double)g[e];
+        g[e] = ad.beta1 * m[e] + (1.f - ad.beta1) * g[e];
+      }
+    }
+    *reinterpret_cast<floatx4*>(bufA + off) = g;
     *reinterpret_cast<intx4*>(bufB + off) = *reinterpret_cast<const intx4*>(Rb + row * 128 + ch * 4);
   }
-  __syncthreads();
+  float r_adam = 1.f;
+  if constexpr (ADAM) {
+    const double tot = block_sum_256(g2, dsum);  // ends with a barrier: the tiles are complete too
+    const double v1 = (double)ad.beta2 * (double)ad.v[b] + (1.0 - (double)ad.beta2) * tot;
+    r_adam = (float)(ad.c1 * sqrt(v1 / ad.c2 + (double)ad.eps));
+    __syncthreads();  // every thread has read v[b]
+    if (tid == 0) ad.v[b] = (float)v1;
+  } else {
+    __syncthreads();
+  }
 
   // element (i, j, r) of this lane: row m, column n of the 128 x 128 result
   auto m_of = [&](int i, int r) { return wm * 64 + i * 32 + ((r >> 2) << 3) + (half << 2) + (r & 3); };
-  auto n_of = [&](int j) { return wn * 64 + j * 32 + l32; };
+  auto n_of = [&](int j) { return wn2 * 64 + j * 32 + l32; };
 
   floatx16 acc[2][2];
-  c128_gemm_nt(bufA, bufB, acc, wm, wn, l32, half);  // M = dR R^T
+  c128_gemm_nt(bufA, bufB, acc, wm, wn2, l32, half);  // P = dR R^T (Adam: M1 R^T)
   __syncthreads();
   float rt[2][2][16], zt[2][2][16];
 #pragma unroll
@@ -114,6 +149,46 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
         acc[i][j][r] = half_lr * (acc[i][j][r] - *reinterpret_cast<const float*>(bufA + c128_addr(n, m)));
       }
   __syncthreads();
+  float bs = 1.f;  // factor of S in the fixed point
+  if constexpr (ADAM) {
+    double s2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s2 += (double)acc[i][j][r] * (double)acc[i][j][r];
+    const double tot = block_sum_256(s2, dsum);
+    const float wn = (float)(sqrt(tot) / (double)r_adam);
+    const float alpha = fminf(ad.lr, 2.f * ad.q / (wn + ad.eps));
+    bs = alpha / (2.f * r_adam);
+    if (ad.scalars_out && tid == 0) {
+      ad.scalars_out[3 * b] = r_adam;
+      ad.scalars_out[3 * b + 1] = alpha;
+      ad.scalars_out[3 * b + 2] = wn;
+    }
+    // M <- S R = S (Rt)^T: S -> bufB, Rt -> bufA
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m_of(i, r), n = n_of(j);
+          *reinterpret_cast<float*>(bufB + c128_addr(m, n)) = acc[i][j][r];
+          *reinterpret_cast<float*>(bufA + c128_addr(m, n)) = rt[i][j][r];
+        }
+    __syncthreads();
+    floatx16 mp[2][2];
+    c128_gemm_nt(bufB, bufA, mp, wm, wn2, l32, half);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Mb[m_of(i, r) * 128 + n_of(j)] = mp[i][j][r];
+    __syncthreads();
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -131,7 +206,7 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
   int used = -1;
   float dprev = 0.f;
   for (int it = 0; it < max_iters; ++it) {
-    c128_gemm_nt(bufA, bufB, acc, wm, wn, l32, half);
+    c128_gemm_nt(bufA, bufB, acc, wm, wn2, l32, half);
     unsigned dmax = 0u;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -139,7 +214,7 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float z = rt[i][j][r] - acc[i][j][r];
+          const float z = rt[i][j][r] - bs * acc[i][j][r];
           dmax = umax(dmax, abs_bits(z - zt[i][j][r]));
           zt[i][j][r] = z;
         }
@@ -189,7 +264,7 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
   if (info && tid == 0) info[b] = used;
 
   if (ortho_err) {  // max |Zt Zt^T - I|: off-diagonal from the fp32 product, diagonal summed in fp64
-    c128_gemm_nt(bufA, bufA, acc, wm, wn, l32, half);
+    c128_gemm_nt(bufA, bufA, acc, wm, wn2, l32, half);
     unsigned e = 0u;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
