@@ -43,6 +43,10 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py against
  * closed forms, brute force and library routines it does not itself use.
+ * kto_cayley_adam_step: the arithmetic of the step is pinned that way too; that its
+ * constants (start value of v, form of the bias correction, q) are those of the cited
+ * algorithm cannot be checked here (the paper prints none of them): parity unpinned
+ * in that respect.
  */
 #include <math.h>
 #include <stdint.h>
