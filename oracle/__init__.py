@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     rotate,
     row_moments,
     loss_grad,
+    pooled_loss_grad,
     cayley_step,
     cayley_step_right,
     cayley_adam_step,

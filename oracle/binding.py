@@ -40,6 +40,8 @@ def _load():
     lib.kto_row_moments.restype = ctypes.c_int
     lib.kto_loss_grad.argtypes = [dp, dp, i64, i64, ctypes.c_double, dp, dp, dp, dp]
     lib.kto_loss_grad.restype = None
+    lib.kto_pooled_loss_grad.argtypes = [dp, dp, i64, i64, ctypes.c_double, ctypes.c_double, dp, dp, dp, dp]
+    lib.kto_pooled_loss_grad.restype = None
     lib.kto_cayley_step.argtypes = [dp, dp, i64, ctypes.c_double, dp, dp]
     lib.kto_cayley_step.restype = ctypes.c_int
     lib.kto_cayley_step_right.argtypes = [dp, dp, i64, ctypes.c_double, dp]
@@ -97,6 +99,19 @@ def loss_grad(X, R, kappa_target=0.0, want_G=False, want_dR=True):
     if want_G:
         out["G"] = G
     return out
+
+
+def pooled_loss_grad(X, R, kappa_target=1.8, rms_eps=0.0, want_G=False, want_dR=True):
+    """Paper-literal pooled loss of one problem.  Returns dict(loss, kappa, G, dR)."""
+    X, R = _d(X), _d(R)
+    n, d = X.shape
+    assert R.shape == (d, d)
+    loss = np.zeros(1); kap = np.zeros(1)
+    G = np.empty((n, d)) if want_G else None
+    dR = np.empty((d, d)) if want_dR else None
+    _load().kto_pooled_loss_grad(_p(X), _p(R), n, d, float(kappa_target), float(rms_eps), _p(loss), _p(kap),
+                                 _p(G), _p(dR))
+    return {"loss": float(loss[0]), "kappa": float(kap[0]), "G": G, "dR": dR}
 
 
 def cayley_step(R, G, lr, want_A=False):

@@ -19,6 +19,12 @@
  *                                          (kurtosis loss of Sec. 2 in its
  *                                           per-token-row reading; gradient by
  *                                           the chain rule through Eq. 3)
+ *   kto_pooled_loss_grad  the loss as the paper writes it: kurtosis of the
+ *                                          concatenation of all tokens' activations
+ *                                          after the linear layer and an RMSNorm,
+ *                                          |kappa - kappa_u| (loss equation of the
+ *                                          "Kurtosis" paragraph; "Learning the
+ *                                          Rotations": linear layer + RMSNorm)
  *   kto_cayley_step     R+ = (I + lr/2 A)^-1 (I - lr/2 A) R,  A = G R^T - R G^T
  *                                          ("Optimization in the Orthogonal
  *                                           Space": Cayley SGD on the Stiefel
@@ -161,6 +167,83 @@ void kto_loss_grad(const double *X, const double *R, int64_t n, int64_t d,
 }
 
 /* C[d][d] = A[d][d] * B[d][d]^T */
+/*
+ * Pooled (paper-literal) kurtosis loss of one problem.
+ *   Y = X R;  rho_i = sqrt(mean_j y_ij^2 + rms_eps);  Z = Y / rho   (RMSNorm, no gain)
+ *   kappa = kurtosis of all n*d entries of Z taken as ONE sample (Eq. 3)
+ *   loss  = |kappa - kappa_target|   (kappa_target == 0: loss = kappa)
+ * Gradient by the chain rule: dL/dz = s 4/(N m2^2) [c^3 - m3 - kappa m2 c], c = z - mu, N = n d;
+ * through the RMSNorm  dL/dy_i = (dL/dz_i)/rho_i - y_i (y_i . dL/dz_i) / (d rho_i^3);  dR = X^T dL/dY.
+ * A row of zeros with rms_eps == 0 is taken as z = 0 with no gradient.
+ * kappa_out, G (n*d, = dL/dY) and dR may each be NULL.
+ */
+void kto_pooled_loss_grad(const double *X, const double *R, int64_t n, int64_t d,
+                          double kappa_target, double rms_eps, double *loss,
+                          double *kappa_out, double *G, double *dR) {
+  const size_t nd = (size_t)n * (size_t)d;
+  double *Y = (double *)malloc(sizeof(double) * nd);
+  double *Z = (double *)malloc(sizeof(double) * nd);
+  double *rho = (double *)malloc(sizeof(double) * (size_t)n);
+  double *Gl = G;
+  if (dR && !Gl) Gl = (double *)malloc(sizeof(double) * nd);
+  kto_rotate(X, R, n, d, Y);
+  for (int64_t i = 0; i < n; ++i) {
+    double s2 = 0.0;
+    for (int64_t j = 0; j < d; ++j) s2 += Y[i * d + j] * Y[i * d + j];
+    rho[i] = sqrt(s2 / (double)d + rms_eps);
+    for (int64_t j = 0; j < d; ++j) Z[i * d + j] = rho[i] > 0.0 ? Y[i * d + j] / rho[i] : 0.0;
+  }
+  const double N = (double)n * (double)d;
+  double mu = 0.0;
+  for (size_t t = 0; t < nd; ++t) mu += Z[t];
+  mu /= N;
+  double m2 = 0.0, m3 = 0.0, m4 = 0.0;
+  for (size_t t = 0; t < nd; ++t) {
+    const double c = Z[t] - mu, c2 = c * c;
+    m2 += c2; m3 += c2 * c; m4 += c2 * c2;
+  }
+  m2 /= N; m3 /= N; m4 /= N;
+  const int degenerate = !(m2 > 0.0);
+  const double kappa = degenerate ? 0.0 : m4 / (m2 * m2);
+  if (kappa_out) *kappa_out = kappa;
+  if (loss) *loss = (kappa_target == 0.0) ? kappa : fabs(kappa - kappa_target);
+  if (Gl) {
+    const double si = (kappa_target == 0.0) ? 1.0 : sgn(kappa - kappa_target);
+    const double a = degenerate ? 0.0 : si * 4.0 / (N * m2 * m2);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+      double *g = Gl + i * d;
+      const double *y = Y + i * d, *z = Z + i * d;
+      if (!(rho[i] > 0.0) || a == 0.0) {
+        for (int64_t j = 0; j < d; ++j) g[j] = 0.0;
+        continue;
+      }
+      double dot = 0.0; /* y_i . dL/dz_i */
+      for (int64_t j = 0; j < d; ++j) {
+        const double c = z[j] - mu;
+        g[j] = a * (c * c * c - m3 - kappa * m2 * c); /* dL/dz */
+        dot += y[j] * g[j];
+      }
+      const double r3 = rho[i] * rho[i] * rho[i];
+      for (int64_t j = 0; j < d; ++j) g[j] = g[j] / rho[i] - y[j] * dot / ((double)d * r3);
+    }
+  }
+  if (dR) {
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < d; ++k) {
+      double *o = dR + k * d;
+      for (int64_t j = 0; j < d; ++j) o[j] = 0.0;
+      for (int64_t i = 0; i < n; ++i) {
+        const double x = X[i * d + k];
+        const double *g = Gl + i * d;
+        for (int64_t j = 0; j < d; ++j) o[j] += x * g[j];
+      }
+    }
+  }
+  free(Y); free(Z); free(rho);
+  if (Gl && Gl != G) free(Gl);
+}
+
 static void mat_abt(const double *A, const double *B, int64_t d, double *C) {
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < d; ++i)
