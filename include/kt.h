@@ -50,7 +50,7 @@ enum {
 };
 
 typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
-typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2 } kt_op;
+typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3 } kt_op;
 
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
@@ -96,6 +96,29 @@ kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64
                                 kt_dtype x_dtype, kt_dtype r_dtype, float kappa_target,
                                 float* loss, float* row_kurt, float* dR,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The loss exactly as the paper writes it (loss equation of the "Kurtosis" paragraph) on the
+ * small network of "Learning the Rotations" (linear layer R followed by an RMSNorm without
+ * gain): with Y = X R, rho_i = sqrt(mean_j y_ij^2 + rms_eps), Z = Y / rho,
+ *
+ *   kappa = kurtosis (Eq. 3) of ALL n*d entries of Z taken as one sample
+ *           (the concatenation of the activations of all tokens),
+ *   loss  = |kappa - kappa_target|   (kappa_target = 1.8, the uniform distribution, in the
+ *           paper; kappa_target == 0 gives loss = kappa),
+ *
+ * per problem of the batch (the paper's 1/L sum over layers is the mean of `loss` over the
+ * batch).  dR = dloss/dR with R a free matrix, including the Jacobian of the RMSNorm.
+ * Arguments as for kt_kurtosis_loss_grad; `kappa` [batch] fp32 or NULL receives kappa.
+ * Three passes over X (moments, recompute + dL/dY, X^T G) for every d, d = 128 included:
+ * the gradient needs the pooled statistics of the whole problem first.
+ * Workspace: kt_workspace_bytes(KT_OP_POOLED_LOSS_GRAD, ...).
+ */
+kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                       int64_t batch, int64_t n, int64_t d,
+                                       kt_dtype x_dtype, kt_dtype r_dtype, float kappa_target,
+                                       float rms_eps, float* loss, float* kappa, float* dR,
+                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * One Cayley SGD step on the orthogonal group ("Optimization in the Orthogonal

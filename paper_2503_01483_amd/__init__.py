@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     KT_OP_LOSS_GRAD,
     KT_OP_CAYLEY,
     KT_OP_FAKEQUANT,
+    KT_OP_POOLED_LOSS_GRAD,
     KtError,
     lib,
     lib_path,
@@ -18,6 +19,7 @@ from .binding import (  # noqa: F401
     kt_last_error,
     kt_workspace_bytes,
     kt_kurtosis_loss_grad,
+    kt_pooled_kurtosis_loss_grad,
     kt_cayley_step,
     kt_cayley_adam_step,
     kt_rotate_fakequant_int4,

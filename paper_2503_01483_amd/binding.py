@@ -9,10 +9,10 @@ _LIB_PATH = os.path.join(_HERE, "libkurtail.so")
 _lib = None
 
 KT_F32, KT_BF16 = 0, 1
-KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT = 0, 1, 2
+KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD = 0, 1, 2, 3
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_profile_enable", "kt_profile_read",
+           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_profile_enable", "kt_profile_read",
            "kt_profile_reset")
 
 
@@ -46,6 +46,9 @@ def lib():
     L.kt_kurtosis_loss_grad.restype = i32
     L.kt_kurtosis_loss_grad.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32,
                                         vp, vp, vp, vp, sz, vp]
+    L.kt_pooled_kurtosis_loss_grad.restype = i32
+    L.kt_pooled_kurtosis_loss_grad.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32, f32, vp, vp, vp,
+                                               vp, sz, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.kt_cayley_adam_step.restype = i32
@@ -137,6 +140,21 @@ def kt_kurtosis_loss_grad(X, R, *, kappa_target=0.0, loss=None, row_kurt=None, d
     _check(lib().kt_kurtosis_loss_grad(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
                                        _dtype_code(R), float(kappa_target), _ptr(loss),
                                        _ptr(row_kurt), _ptr(dR), _ptr(ws), ws.numel(), _stream(stream)))
+    return loss
+
+
+def kt_pooled_kurtosis_loss_grad(X, R, *, kappa_target=1.8, rms_eps=0.0, loss=None, kappa=None, dR=None,
+                                 workspace=None, stream=None):
+    """Paper-literal pooled loss [batch] fp32 (returned), optional kappa [batch] and dR outputs."""
+    X, R, batch, n, d = _xr_dims(X, R)
+    if loss is None:
+        loss = torch.empty(batch, dtype=torch.float32, device=X.device)
+    xdt = _dtype_code(X)
+    need = kt_workspace_bytes(KT_OP_POOLED_LOSS_GRAD, batch, n, d, xdt)
+    ws = (workspace or Workspace(X.device)).get(need)
+    _check(lib().kt_pooled_kurtosis_loss_grad(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
+                                              _dtype_code(R), float(kappa_target), float(rms_eps), _ptr(loss),
+                                              _ptr(kappa), _ptr(dR), _ptr(ws), ws.numel(), _stream(stream)))
     return loss
 
 

@@ -131,15 +131,15 @@ struct LossGradPlan {
   int P;           // moment partials per token
   int tiles_dd;    // tiles of the d x d output GEMM
   int slabs_per_split, split_k;
-  size_t o_rt, o_part, o_coef, o_losspart, o_xt, o_gt, o_splitk, total;
+  size_t o_rt, o_part, o_coef, o_losspart, o_xt, o_gt, o_splitk, o_gstat, total;
   int loss_blocks;
 };
 
-static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
+static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype xdt, bool pooled = false) {
   LossGradPlan p;
   p.fp32 = (xdt == KT_F32);
   p.esz = p.fp32 ? 4 : 2;
-  p.fused = !p.fp32 && d == 128;
+  p.fused = !p.fp32 && d == 128 && !pooled;  // the pooled loss needs its global statistics before the gradient
   p.fused_wgs = 0;
   if (p.fused) {
     const int64_t tiles = ceil_div(n, kF128Tile);
@@ -151,7 +151,7 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
     p.o_rt = c.take((size_t)batch * d * d * p.esz);
     p.o_losspart = c.take((size_t)batch * p.fused_wgs * 8);
     p.o_splitk = c.take((size_t)p.fused_wgs * batch * d * d * 4);
-    p.o_part = p.o_coef = p.o_xt = p.o_gt = 0;
+    p.o_part = p.o_coef = p.o_xt = p.o_gt = p.o_gstat = 0;
     p.total = c.off;
     return p;
   }
@@ -181,7 +181,8 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   p.o_rt = c.take((size_t)batch * d * d * p.esz);
   p.o_part = c.take((size_t)batch * p.P * n * 16);
   p.o_coef = c.take((size_t)batch * n * 16);
-  p.o_losspart = c.take((size_t)batch * p.loss_blocks * 8);
+  p.o_losspart = c.take((size_t)batch * p.loss_blocks * 8 * (pooled ? 4 : 1));
+  p.o_gstat = c.take(pooled ? (size_t)batch * 4 * 8 : 0);
   p.o_xt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
   p.o_gt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
   p.o_splitk = c.take(p.split_k > 1 ? (size_t)p.split_k * batch * d * d * 4 : 0);
@@ -299,11 +300,16 @@ static bool prep_rt(const void* R, int64_t ldr, kt_dtype rdt, Tout* RT, int64_t 
 }
 
 // ------------------------------------------------------------------ loss + grad ---
+struct PooledArgs {  // paper-literal pooled loss (kurtosis over all entries after an RMSNorm)
+  float rms_eps;
+  float* kappa_out;  // [batch] or null
+};
+
 template <typename T, class TFWD, class TDD>
 static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx, const void* R,
                                int64_t ldr, kt_dtype rdt, int64_t batch, int64_t n, int64_t d,
                                float kappa_target, float* loss, float* row_kurt, float* dR,
-                               char* ws, hipStream_t st) {
+                               char* ws, hipStream_t st, const PooledArgs* pooled = nullptr) {
   T* RT = reinterpret_cast<T*>(ws + p.o_rt);
   floatx4* part = reinterpret_cast<floatx4*>(ws + p.o_part);
   floatx4* coef = reinterpret_cast<floatx4*>(ws + p.o_coef);
@@ -324,6 +330,19 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
     if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
       return fail(KT_ERR_DEVICE, "forward GEMM launch failed");
   }
+  if (pooled) {
+    // a2, pooled form: pooled sums -> global statistics and loss -> per-token coefficients
+    double* gstat = reinterpret_cast<double*>(ws + p.o_gstat);
+    hipLaunchKernelGGL(pooled_stage1_kernel, dim3(p.loss_blocks, (unsigned)batch), dim3(256), 0, st, part, p.P,
+                       (int)n, (int)d, pooled->rms_eps, loss_part);
+    hipLaunchKernelGGL(pooled_stage2_kernel, dim3((unsigned)batch), dim3(256), 0, st, loss_part, p.loss_blocks,
+                       (int)n, (int)d, kappa_target, gstat, loss, pooled->kappa_out);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "pooled statistics launch failed");
+    if (!dR) return KT_OK;
+    hipLaunchKernelGGL(pooled_stage3_kernel, dim3(p.loss_blocks, (unsigned)batch), dim3(256), 0, st, part, p.P,
+                       (int)n, (int)d, pooled->rms_eps, gstat, coef);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "pooled coefficient launch failed");
+  } else {
   // a2: per-token finalisation and loss
   hipLaunchKernelGGL(finalize_rows_kernel, dim3(p.loss_blocks, (unsigned)batch), dim3(256), 0, st, part,
                      p.P, (int)n, (int)d, kappa_target, coef, row_kurt, loss_part);
@@ -332,6 +351,7 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
                      p.loss_blocks, (int)n, loss);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "finalize_loss launch failed");
   if (!dR) return KT_OK;
+  }
 
   // token-minor copy of X for the last GEMM (zero padded to ldt tokens)
   {
@@ -613,6 +633,9 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
     case KT_OP_LOSS_GRAD:
       if (n < 1) return 0;
       return plan_loss_grad(batch, n, d, x_dtype).total;
+    case KT_OP_POOLED_LOSS_GRAD:
+      if (n < 1) return 0;
+      return plan_loss_grad(batch, n, d, x_dtype, true).total;
     case KT_OP_CAYLEY:
       return plan_cayley(batch, d).total;
     case KT_OP_FAKEQUANT:
@@ -648,6 +671,34 @@ kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64
                                                loss, row_kurt, dR, ws, st);
   return run_loss_grad<bf16, TB_M128, TB_128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target,
                                               loss, row_kurt, dR, ws, st);
+}
+
+kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                       int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype,
+                                       kt_dtype r_dtype, float kappa_target, float rms_eps, float* loss,
+                                       float* kappa, float* dR, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+  g_err[0] = 0;
+  kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
+  if (s != KT_OK) return s;
+  if (!loss) return fail(KT_ERR_INVALID_ARG, "loss must not be null");
+  if (!(kappa_target >= 0.f)) return fail(KT_ERR_INVALID_ARG, "kappa_target must be >= 0");
+  if (!(rms_eps >= 0.f)) return fail(KT_ERR_INVALID_ARG, "rms_eps must be >= 0");
+  const LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype, true);
+  s = check_ws(workspace, workspace_bytes, p.total);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  PooledArgs pa;
+  pa.rms_eps = rms_eps; pa.kappa_out = kappa;
+  if (p.fp32)
+    return run_loss_grad<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss, nullptr,
+                                        dR, ws, st, &pa);
+  if (d % 256 == 0)
+    return run_loss_grad<bf16, TB_BIG, TB_BIG>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss,
+                                               nullptr, dR, ws, st, &pa);
+  return run_loss_grad<bf16, TB_M128, TB_128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, kappa_target, loss,
+                                              nullptr, dR, ws, st, &pa);
 }
 
 kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d, float lr,

@@ -175,6 +175,109 @@ __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __res
   if (threadIdx.x == 0) loss_part[(int64_t)batch * gridDim.x + blockIdx.x] = s;
 }
 
+// ---- pooled (paper-literal) loss: kurtosis of ALL entries of RMSNorm(X R) as one sample ------
+// Row sums of z^k = (y / rho)^k follow from the row's raw sums of y^k, so the forward GEMM with the
+// moment epilogue is used unchanged.  Stage 1: per token rho and the block partials of the four
+// pooled raw sums.  grid = (ceil(n/256), batch).
+__device__ __forceinline__ void pooled_row_sums(const floatx4* __restrict__ part, int P, int n, int64_t batch,
+                                                int token, int d, double rms_eps, double& inv_rho,
+                                                double (&Z)[4]) {
+  double S1 = 0, S2 = 0, S3 = 0, S4 = 0;
+  for (int p = 0; p < P; ++p) {
+    const floatx4 v = part[((int64_t)batch * P + p) * n + token];
+    S1 += v[0]; S2 += v[1]; S3 += v[2]; S4 += v[3];
+  }
+  const double rho2 = S2 / (double)d + rms_eps;
+  inv_rho = rho2 > 0.0 ? 1.0 / sqrt(rho2) : 0.0;  // a row of zeros: z = 0
+  const double i2 = inv_rho * inv_rho;
+  Z[0] = S1 * inv_rho; Z[1] = S2 * i2; Z[2] = S3 * i2 * inv_rho; Z[3] = S4 * i2 * i2;
+}
+
+__global__ __launch_bounds__(256) void pooled_stage1_kernel(const floatx4* __restrict__ part, int P, int n, int d,
+                                                            float rms_eps, double* __restrict__ pool_part) {
+  __shared__ double sh[256];
+  const int batch = blockIdx.y, token = blockIdx.x * 256 + threadIdx.x;
+  double Z[4] = {0, 0, 0, 0}, inv_rho;
+  if (token < n) pooled_row_sums(part, P, n, batch, token, d, (double)rms_eps, inv_rho, Z);
+  for (int k = 0; k < 4; ++k) {
+    const double t = block_sum_256(Z[k], sh);
+    if (threadIdx.x == 0) pool_part[(((int64_t)batch * gridDim.x + blockIdx.x) << 2) + k] = t;
+    __syncthreads();
+  }
+}
+
+// Stage 2: pooled moments, kappa, loss; gstat[batch] = {mu, m3, beta = kappa m2, A = s 4/(N m2^2)}.
+// grid = batch.
+__global__ __launch_bounds__(256) void pooled_stage2_kernel(const double* __restrict__ pool_part, int nblocks,
+                                                            int n, int d, float kappa_target,
+                                                            double* __restrict__ gstat, float* __restrict__ loss,
+                                                            float* __restrict__ kappa_out) {
+  __shared__ double sh[256];
+  const int batch = blockIdx.x;
+  double T[4];
+  for (int k = 0; k < 4; ++k) {
+    double v = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += 256) v += pool_part[(((int64_t)batch * nblocks + i) << 2) + k];
+    T[k] = block_sum_256(v, sh);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double N = (double)n * (double)d;
+    const double mu = T[0] / N, r2 = T[1] / N, r3 = T[2] / N, r4 = T[3] / N;
+    const double m2 = r2 - mu * mu;
+    const double m3 = r3 - 3.0 * mu * r2 + 2.0 * mu * mu * mu;
+    const double m4 = r4 - 4.0 * mu * r3 + 6.0 * mu * mu * r2 - 3.0 * mu * mu * mu * mu;
+    double kappa = 0.0, A = 0.0, term = 0.0;
+    if (m2 > 1e-7 * r2) {
+      kappa = m4 / (m2 * m2);
+      double sgn = 1.0;
+      if (kappa_target != 0.f) {
+        const double dk = kappa - (double)kappa_target;
+        sgn = (dk > 0.0) - (dk < 0.0);
+        term = fabs(dk);
+      } else {
+        term = kappa;
+      }
+      A = sgn * 4.0 / (N * m2 * m2);
+    } else if (kappa_target != 0.f) {
+      term = fabs((double)kappa_target);
+    }
+    gstat[4 * batch] = mu; gstat[4 * batch + 1] = m3; gstat[4 * batch + 2] = kappa * m2; gstat[4 * batch + 3] = A;
+    loss[batch] = (float)term;
+    if (kappa_out) kappa_out[batch] = (float)kappa;
+  }
+}
+
+// Stage 3: per token, the coefficients of the backward epilogue.  With c' = y - rho mu the gradient
+// through the RMSNorm, (g - z (z.g)/d) / rho with g = A [c^3 - m3 - beta c], c = z - mu, is again
+//   alpha' [ c'^3 - m3' - beta' c' ],  alpha' = A / rho^4,  beta' = (beta + tau) rho^2,
+//   m3' = (m3 + tau mu) rho^3,  tau = (1/d) sum_j z [c^3 - m3 - beta c]  (from the row's sums of z^k),
+// so the recompute GEMM and its epilogue are the per-row ones.  grid = (ceil(n/256), batch).
+__global__ __launch_bounds__(256) void pooled_stage3_kernel(const floatx4* __restrict__ part, int P, int n, int d,
+                                                            float rms_eps, const double* __restrict__ gstat,
+                                                            floatx4* __restrict__ coef) {
+  const int batch = blockIdx.y, token = blockIdx.x * 256 + threadIdx.x;
+  if (token >= n) return;
+  double Z[4], inv_rho;
+  pooled_row_sums(part, P, n, batch, token, d, (double)rms_eps, inv_rho, Z);
+  const double mu = gstat[4 * batch], m3 = gstat[4 * batch + 1], beta = gstat[4 * batch + 2], A = gstat[4 * batch + 3];
+  floatx4 c = {0.f, 0.f, 0.f, 0.f};
+  if (inv_rho > 0.0 && A != 0.0) {
+    const double dd = (double)d, mu2 = mu * mu;
+    const double C1 = Z[0] - dd * mu;
+    const double C2 = Z[1] - 2.0 * mu * Z[0] + dd * mu2;
+    const double C3 = Z[2] - 3.0 * mu * Z[1] + 3.0 * mu2 * Z[0] - dd * mu2 * mu;
+    const double C4 = Z[3] - 4.0 * mu * Z[2] + 6.0 * mu2 * Z[1] - 4.0 * mu2 * mu * Z[0] + dd * mu2 * mu2;
+    const double tau = (C4 + mu * C3 - m3 * Z[0] - beta * (C2 + mu * C1)) / dd;
+    const double rho = 1.0 / inv_rho, i2 = inv_rho * inv_rho;
+    c[0] = (float)(A * i2 * i2);
+    c[1] = (float)(rho * mu);
+    c[2] = (float)((beta + tau) * rho * rho);
+    c[3] = (float)((m3 + tau * mu) * rho * rho * rho);
+  }
+  coef[(int64_t)batch * n + token] = c;
+}
+
 // loss[batch] = (sum of the block partials, fixed order) / n.  grid = batch blocks.
 __global__ __launch_bounds__(256) void finalize_loss_kernel(const double* __restrict__ loss_part,
                                                             int nblocks, int n,
