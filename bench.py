@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
+    ap.add_argument("--loss", choices=["row", "pooled"], default="row",
+                    help="per-token-row kurtosis (default, the headline step) or the paper-literal pooled loss "
+                         "with RMSNorm (kappa_target 1.8)")
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
                     help="retraction timed inside the step: Cayley SGD (default, the headline step) or Cayley Adam")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -66,7 +69,9 @@ def main():
     bf16 = cfg["dtype"] == "bf16"
 
     ws = kt.Workspace(dev)
-    ws.get(max(kt.kt_workspace_bytes(kt.KT_OP_LOSS_GRAD, batch, n, d, kt.KT_BF16 if bf16 else kt.KT_F32),
+    pooled = args.loss == "pooled"
+    ws.get(max(kt.kt_workspace_bytes(kt.KT_OP_POOLED_LOSS_GRAD if pooled else kt.KT_OP_LOSS_GRAD, batch, n, d,
+                                     kt.KT_BF16 if bf16 else kt.KT_F32),
                kt.kt_workspace_bytes(kt.KT_OP_CAYLEY, batch, 0, d, kt.KT_F32)))
     loss = torch.zeros(batch, device=dev)
     dR = torch.empty((batch, d, d), device=dev)
@@ -78,7 +83,10 @@ def main():
     counter = [0]
 
     def step():
-        kt.kt_kurtosis_loss_grad(X, Rw, loss=loss, dR=dR, workspace=ws)
+        if pooled:
+            kt.kt_pooled_kurtosis_loss_grad(X, Rw, loss=loss, dR=dR, workspace=ws)
+        else:
+            kt.kt_kurtosis_loss_grad(X, Rw, loss=loss, dR=dR, workspace=ws)
         if args.no_cayley:
             return
         if adam:
@@ -118,7 +126,7 @@ def main():
         if cnt:
             kern[k] = {"avg_ms": tot / cnt, "launches": cnt, "tflops": flops_launch / (tot / cnt * 1e-3) / 1e12}
     dom = max(kern, key=lambda k: kern[k]["avg_ms"])
-    fused = bf16 and d == 128   # single-pass kernel: reads X once, bound by HBM rather than by the matrix pipe
+    fused = bf16 and d == 128 and not pooled   # single-pass kernel: reads X once, bound by HBM rather than by the matrix pipe
     if fused:
         x_bytes = 2.0 * batch * n * d
         gbs = x_bytes / (kern[0]["avg_ms"] * 1e-3) / 1e9
@@ -142,7 +150,7 @@ def main():
     hw_tflops = 6.0 * batch * n * d * d * args.steps / elapsed / 1e12
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not pooled:
         import numpy as np
         import oracle
         rows = min(n, CPU_SAMPLE_ROWS[args.config])
@@ -169,7 +177,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: n={n} tokens x d={d}, batch={batch}, "
-                               f"loss+grad{'' if args.no_cayley else ('+Cayley Adam' if adam else '+Cayley')} step, lr={lr}",
+                               f"{'pooled ' if pooled else ''}loss+grad{'' if args.no_cayley else ('+Cayley Adam' if adam else '+Cayley')} step, lr={lr}",
                    "global_batch": batch * n, "hidden": d},
         "tflops_algorithmic_4nd2": round(alg_tflops, 2),
         "tflops_hardware_6nd2": None if fused else round(hw_tflops, 2),
