@@ -17,4 +17,5 @@ from .binding import (  # noqa: F401
     cayley_step_right,
     cayley_adam_step,
     fakequant_int4,
+    quant_metrics,
 )

@@ -49,6 +49,8 @@ def _load():
     cd = ctypes.c_double
     lib.kto_cayley_adam_step.argtypes = [dp, dp, dp, cd, i64, i64, cd, cd, cd, cd, cd, dp, dp, dp, dp]
     lib.kto_cayley_adam_step.restype = ctypes.c_int
+    lib.kto_quant_metrics.argtypes = [dp, dp, fp, i64, i64, ctypes.c_double, fp, fp, dp, dp]
+    lib.kto_quant_metrics.restype = ctypes.c_int64
     lib.kto_fakequant_int4.argtypes = [dp, dp, i64, i64, ctypes.c_float, fp, fp, i8p, dp]
     lib.kto_fakequant_int4.restype = None
     _lib = lib
@@ -167,3 +169,22 @@ def fakequant_int4(X, R, clip=1.0, scales_in=None):
     _load().kto_fakequant_int4(_p(X), _p(R), n, d, float(clip), _p(sin, ctypes.c_float),
                                _p(sout, ctypes.c_float), _p(codes, ctypes.c_int8), _p(err))
     return {"scales": sout, "codes": codes, "err": err}
+
+
+def quant_metrics(X, R, quantile=0.98, Y=None):
+    """Per-token quantisation-quality figures.  Y (float32 [n][d]) replaces X R when given.
+    Returns dict(success int, amax float32[n][2], thr float32[n], err_sym, err_asym float64[n][2])."""
+    X, R = _d(X), _d(R)
+    n, d = X.shape
+    Yf = None
+    if Y is not None:
+        Yf = np.ascontiguousarray(np.asarray(Y, dtype=np.float32))
+        assert Yf.shape == (n, d)
+    amax = np.empty((n, 2), dtype=np.float32)
+    thr = np.empty(n, dtype=np.float32)
+    es = np.empty((n, 2), dtype=np.float64)
+    ea = np.empty((n, 2), dtype=np.float64)
+    succ = _load().kto_quant_metrics(_p(X), _p(R), _p(Yf, ctypes.c_float), n, d, float(quantile),
+                                     _p(amax, ctypes.c_float), _p(thr, ctypes.c_float), _p(es), _p(ea))
+    return {"success": int(succ), "amax": amax, "thr": thr, "err_sym": es, "err_asym": ea}
+

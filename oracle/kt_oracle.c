@@ -44,6 +44,14 @@
  *                                           s = max|x| / (2^(k-1) - 1); MSE of
  *                                           Eq. 1; Setup: one scale per row)
  *
+ *   kto_quant_metrics   per-token quantisation-quality figures of Y = X R: largest
+ *                                          magnitude before / after the rotation (the
+ *                                          "success rate" of "Evaluation of ... on Channel
+ *                                          Outliers"), symmetric int4 error with the scale
+ *                                          clipped at a quantile of |y| (Setup: quantile
+ *                                          0.98), asymmetric int4 error (Background:
+ *                                          b = min, s = (max - min)/(2^k - 1); Setup: KV)
+ *
  * Degenerate rows (no spread: m2 <= 1e-30 * mean(y^2), or an all-zero row):
  * kappa := 0, gradient row := 0, the row still counts in the 1/n.
  *
@@ -500,3 +508,98 @@ void kto_fakequant_int4(const double *X, const double *R, int64_t n, int64_t d,
   }
   free(Y);
 }
+
+static int cmp_float(const void *a, const void *b) {
+  const float x = *(const float *)a, y = *(const float *)b;
+  return (x > y) - (x < y);
+}
+
+/*
+ * Per token row of Y = X R (or of Y_in, n*d floats, when given: the rotation is then skipped
+ * and y = (double)Y_in), with yf = (float)y and every rounding-critical step in IEEE single:
+ *   amax[i]   = { max_j |x_ij| as float, max_j |yf_ij| };   success = amax_rot < amax_base
+ *   symmetric int4, scale clipped at the quantile `quant` of |yf| over the row (linear
+ *   interpolation between order statistics: pos = quant (d-1), k = floor(pos),
+ *   t = a_k + (float)(pos - k) (a_{k+1} - a_k) on the ascending a; quant >= 1: t = amax):
+ *     s = t / 7.0f, r = 1.0f / s, q = clamp(rint(yf r), -7, 7), yhat = q s
+ *   asymmetric int4:  b = min_j yf, s = (max_j yf - b) / 15.0f, r = 1.0f / s,
+ *     q = clamp(rint((yf - b) r), 0, 15), yhat = q s + b
+ *   err_sym[i] = err_asym[i] = { sum_j (y - yhat)^2, sum_j y^2 } in fp64.
+ * A row with s == 0 reproduces itself for asym (yhat = b) and gives yhat = 0 for sym.
+ * Returns the number of successes.  Output pointers may be NULL.
+ */
+int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, int64_t n, int64_t d,
+                          double quant, float *amax, float *thr, double *err_sym, double *err_asym) {
+  double *Y = NULL;
+  if (!Y_in) {
+    Y = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
+    kto_rotate(X, R, n, d, Y);
+  }
+  int64_t succ = 0;
+#pragma omp parallel for schedule(static) reduction(+ : succ)
+  for (int64_t i = 0; i < n; ++i) {
+    float *a = (float *)malloc(sizeof(float) * (size_t)d);
+    float ab = 0.0f, ar = 0.0f, mn = 0.0f, mx = 0.0f;
+    double y2 = 0.0;
+    for (int64_t j = 0; j < d; ++j) {
+      const double yd = Y_in ? (double)Y_in[i * d + j] : Y[i * d + j];
+      const float yf = (float)yd;
+      const float xa = fabsf((float)X[i * d + j]);
+      if (xa > ab) ab = xa;
+      a[j] = fabsf(yf);
+      if (a[j] > ar) ar = a[j];
+      if (j == 0 || yf < mn) mn = yf;
+      if (j == 0 || yf > mx) mx = yf;
+      y2 += yd * yd;
+    }
+    if (ar < ab) succ += 1;
+    if (amax) { amax[2 * i] = ab; amax[2 * i + 1] = ar; }
+    float t = ar;
+    if (quant < 1.0) {
+      qsort(a, (size_t)d, sizeof(float), cmp_float);
+      const double pos = quant * (double)(d - 1);
+      const int64_t k = (int64_t)floor(pos);
+      const float frac = (float)(pos - (double)k);
+      const float hi = a[k + 1 < d ? k + 1 : k];
+      volatile float diff = hi - a[k];
+      volatile float inc = frac * diff;
+      t = a[k] + inc;
+    }
+    if (thr) thr[i] = t;
+    const float ss = t / 7.0f;
+    volatile float span = mx - mn;
+    const float sa = span / 15.0f;
+    double es = 0.0, ea = 0.0;
+    for (int64_t j = 0; j < d; ++j) {
+      const double yd = Y_in ? (double)Y_in[i * d + j] : Y[i * d + j];
+      const float yf = (float)yd;
+      double yh = 0.0;
+      if (ss > 0.0f) {
+        volatile float r = 1.0f / ss;
+        volatile float u = yf * r;
+        float q = rintf(u);
+        if (q > 7.0f) q = 7.0f;
+        if (q < -7.0f) q = -7.0f;
+        yh = (double)q * (double)ss;
+      }
+      es += (yd - yh) * (yd - yh);
+      double ya = (double)mn;
+      if (sa > 0.0f) {
+        volatile float r = 1.0f / sa;
+        volatile float c = yf - mn;
+        volatile float u = c * r;
+        float q = rintf(u);
+        if (q > 15.0f) q = 15.0f;
+        if (q < 0.0f) q = 0.0f;
+        ya = (double)q * (double)sa + (double)mn;
+      }
+      ea += (yd - ya) * (yd - ya);
+    }
+    if (err_sym) { err_sym[2 * i] = es; err_sym[2 * i + 1] = y2; }
+    if (err_asym) { err_asym[2 * i] = ea; err_asym[2 * i + 1] = y2; }
+    free(a);
+  }
+  if (Y) free(Y);
+  return succ;
+}
+
