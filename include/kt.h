@@ -50,7 +50,8 @@ enum {
 };
 
 typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
-typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3 } kt_op;
+typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3,
+               KT_OP_QUANT_METRICS = 4 } kt_op;
 
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
@@ -197,6 +198,32 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
                                    const float* scales_in, float* scales_out, int8_t* codes,
                                    float* err, void* workspace, size_t workspace_bytes,
                                    void* stream);
+
+/*
+ * Per-token quantisation-quality figures of the rotated activations Y = X R, the quantities
+ * the paper evaluates a rotation with:
+ *   amax      [batch][n][2] fp32 {max_j |x_ij|, max_j |y_ij|};  success[batch] int64 = number of
+ *             tokens whose largest magnitude shrank ("Evaluation ... on Channel Outliers": the
+ *             success rate is success / n)
+ *   threshold [batch][n] fp32: the `quantile` quantile of |y_i| over the row (linear interpolation
+ *             between order statistics; quantile = 1: the maximum).  Setup appendix: 0.98.
+ *   err_sym   [batch][n][2] fp32 {sum_j (y - yhat)^2, sum_j y^2}, symmetric int4 with
+ *             s = threshold / 7, values beyond the threshold clipped (Background, "Uniform
+ *             Quantization for k-bit Precision", b = 0; Setup: per-token, clipped at a quantile)
+ *   err_asym  [batch][n][2] fp32, asymmetric int4: b = min_j y, s = (max_j y - b) / 15
+ *             (Background; Setup: KV caches)
+ *   Y         [batch][n][d] fp32: receives the rotated activations, or NULL (then they live in
+ *             the workspace).  Every output pointer may be NULL.
+ * Y is materialised (this is an evaluation tool, not the training step): one GEMM pass, then one
+ * workgroup per token with the row in LDS (radix select for the quantile).  d <= 8192.
+ * Workspace: kt_workspace_bytes(KT_OP_QUANT_METRICS, ...) (sized for Y == NULL).
+ */
+kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                                  int64_t batch, int64_t n, int64_t d,
+                                  kt_dtype x_dtype, kt_dtype r_dtype, float quantile,
+                                  float* Y, float* amax, float* threshold, float* err_sym,
+                                  float* err_asym, int64_t* success,
+                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid (not part of the method; off by default).  When enabled, the

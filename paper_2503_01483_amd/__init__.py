@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     KT_OP_CAYLEY,
     KT_OP_FAKEQUANT,
     KT_OP_POOLED_LOSS_GRAD,
+    KT_OP_QUANT_METRICS,
     KtError,
     lib,
     lib_path,
@@ -23,6 +24,7 @@ from .binding import (  # noqa: F401
     kt_cayley_step,
     kt_cayley_adam_step,
     kt_rotate_fakequant_int4,
+    kt_rotate_quant_metrics,
     Workspace,
     kt_profile_enable,
     kt_profile_read,

@@ -9,10 +9,10 @@ _LIB_PATH = os.path.join(_HERE, "libkurtail.so")
 _lib = None
 
 KT_F32, KT_BF16 = 0, 1
-KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD = 0, 1, 2, 3
+KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD, KT_OP_QUANT_METRICS = 0, 1, 2, 3, 4
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_profile_enable", "kt_profile_read",
+           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_profile_enable", "kt_profile_read",
            "kt_profile_reset")
 
 
@@ -49,6 +49,9 @@ def lib():
     L.kt_pooled_kurtosis_loss_grad.restype = i32
     L.kt_pooled_kurtosis_loss_grad.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32, f32, vp, vp, vp,
                                                vp, sz, vp]
+    L.kt_rotate_quant_metrics.restype = i32
+    L.kt_rotate_quant_metrics.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp,
+                                          vp, sz, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.kt_cayley_adam_step.restype = i32
@@ -198,6 +201,18 @@ def kt_rotate_fakequant_int4(X, R, *, clip_ratio=1.0, scales_in=None, scales_out
                                           _dtype_code(R), float(clip_ratio), _ptr(scales_in),
                                           _ptr(scales_out), _ptr(codes), _ptr(err), _ptr(ws),
                                           ws.numel(), _stream(stream)))
+
+
+def kt_rotate_quant_metrics(X, R, *, quantile=0.98, Y=None, amax=None, threshold=None, err_sym=None,
+                            err_asym=None, success=None, workspace=None, stream=None):
+    X, R, batch, n, d = _xr_dims(X, R)
+    xdt = _dtype_code(X)
+    need = kt_workspace_bytes(KT_OP_QUANT_METRICS, batch, n, d, xdt)
+    ws = (workspace or Workspace(X.device)).get(need)
+    _check(lib().kt_rotate_quant_metrics(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
+                                         _dtype_code(R), float(quantile), _ptr(Y), _ptr(amax), _ptr(threshold),
+                                         _ptr(err_sym), _ptr(err_asym), _ptr(success), _ptr(ws), ws.numel(),
+                                         _stream(stream)))
 
 
 def kt_profile_enable(max_records):

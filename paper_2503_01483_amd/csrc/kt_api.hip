@@ -636,6 +636,9 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
     case KT_OP_POOLED_LOSS_GRAD:
       if (n < 1) return 0;
       return plan_loss_grad(batch, n, d, x_dtype, true).total;
+    case KT_OP_QUANT_METRICS:
+      if (n < 1) return 0;
+      return round_up(batch * d * d * (x_dtype == KT_F32 ? 4 : 2), 256) + (size_t)batch * n * d * 4;
     case KT_OP_CAYLEY:
       return plan_cayley(batch, d).total;
     case KT_OP_FAKEQUANT:
@@ -787,6 +790,52 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
                                            scales_out, codes, err, ws, st);
   return run_quant<bf16, TB_M128, TB_N128>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
                                            scales_out, codes, err, ws, st);
+}
+
+kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int64_t ldr, int64_t batch,
+                                  int64_t n, int64_t d, kt_dtype x_dtype, kt_dtype r_dtype, float quantile,
+                                  float* Y, float* amax, float* threshold, float* err_sym, float* err_asym,
+                                  int64_t* success, void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
+  if (s != KT_OK) return s;
+  if (!(quantile > 0.f && quantile <= 1.f)) return fail(KT_ERR_INVALID_ARG, "quantile must be in (0, 1]");
+  if (d > 8192) return fail(KT_ERR_NOT_SUPPORTED, "quantisation metrics keep a token row in LDS: d <= 8192");
+  const bool fp32 = x_dtype == KT_F32;
+  const size_t rt_bytes = (size_t)round_up(batch * d * d * (fp32 ? 4 : 2), 256);
+  const size_t need = rt_bytes + (Y ? 0 : (size_t)batch * n * d * 4);
+  s = check_ws(workspace, workspace_bytes, need);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* Yb = Y ? Y : reinterpret_cast<float*>(ws + rt_bytes);
+  ProfScope prof(5, st);
+  // Y = X R, token-major (tokens on the rows of the GEMM): Y never feeds another GEMM here, the
+  // row kernel wants whole token rows
+  auto rotate = [&](auto t_tag, auto tile_tag) -> kt_status {
+    using T = decltype(t_tag);
+    using TL = decltype(tile_tag);
+    T* RT = reinterpret_cast<T*>(ws);
+    if (!prep_rt<T>(R, ldr, r_dtype, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
+    EpiStore<TL> e;
+    e.C = Yb; e.ldc = d; e.batch_stride = n * d; e.split_stride = 0; e.M = (int)n; e.N = (int)d;
+    if (!launch_gemm<TL>(static_cast<const T*>(X), ldx, n * ldx, (int)n, RT, d, d * d, (int)d, d, 0, (int)batch, e,
+                         st))
+      return fail(KT_ERR_DEVICE, "rotation GEMM launch failed");
+    if (success) {
+      hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<unsigned*>(success),
+                         2 * batch, 0u);
+    }
+    hipLaunchKernelGGL((quant_metrics_row_kernel<T>), dim3((unsigned)n, (unsigned)batch), dim3(256),
+                       (size_t)d * 4, st, Yb, static_cast<const T*>(X), ldx, n * ldx, (int)n, (int)d,
+                       (double)quantile, amax, threshold, err_sym, err_asym,
+                       reinterpret_cast<unsigned long long*>(success));
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "metrics kernel launch failed");
+    return KT_OK;
+  };
+  if (fp32) return rotate(float{}, TF{});
+  if (d % 256 == 0) return rotate(bf16{}, TB_BIG{});
+  return rotate(bf16{}, TB_N128{});
 }
 
 kt_status kt_profile_reset(void) {

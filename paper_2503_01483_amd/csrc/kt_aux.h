@@ -573,4 +573,143 @@ __global__ __launch_bounds__(256) void quant_err_kernel(const float2* __restrict
   err[batch * n + t] = make_float2(e, y);
 }
 
+// ---- per-token quantisation-quality figures of a materialised Y = X R ----------------------
+// (max-value "success" of "Evaluation ... on Channel Outliers"; Setup: symmetric per-token
+// quantisation clipped at a quantile, asymmetric quantisation for KV caches; Background:
+// "Uniform Quantization for k-bit Precision".)  One workgroup per token row, the row in LDS.
+// Every rounding-critical step is a single IEEE fp32 operation, as in the symmetric fake-quant.
+__device__ __forceinline__ float block_fmax_256(float v, float* red4) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red4[0], red4[1]), fmaxf(red4[2], red4[3]));
+}
+__device__ __forceinline__ unsigned block_umin_256(unsigned v, unsigned* red4) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const unsigned w = (unsigned)__shfl_xor((int)v, o);
+    v = w < v ? w : v;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const unsigned a = red4[0] < red4[1] ? red4[0] : red4[1], b = red4[2] < red4[3] ? red4[2] : red4[3];
+  return a < b ? a : b;
+}
+
+// grid = (n, batch); dynamic LDS = d * 4 bytes.  Y [batch][n][d] fp32.
+template <typename TX>
+__global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __restrict__ Y,
+                                                                const TX* __restrict__ X, int64_t ldx,
+                                                                int64_t x_batch_stride, int n, int d,
+                                                                double quant, float* __restrict__ amax_out,
+                                                                float* __restrict__ thr_out,
+                                                                float* __restrict__ err_sym,
+                                                                float* __restrict__ err_asym,
+                                                                unsigned long long* __restrict__ success) {
+  extern __shared__ __align__(16) float row[];
+  __shared__ unsigned hist[256];
+  __shared__ double shd[256];
+  __shared__ float red4[4];
+  __shared__ unsigned ured4[4];
+  __shared__ unsigned sel[2];
+  const int tid = threadIdx.x, batch = blockIdx.y, token = blockIdx.x;
+  const float* y = Y + ((int64_t)batch * n + token) * d;
+  const TX* x = X + (int64_t)batch * x_batch_stride + (int64_t)token * ldx;
+  float ab = 0.f, ar = 0.f, mn = 3.0e38f, mx = -3.0e38f;
+  double y2 = 0.0;
+  for (int j = tid; j < d; j += 256) {
+    const float v = y[j];
+    row[j] = v;
+    ab = fmaxf(ab, fabsf((float)x[j]));
+    ar = fmaxf(ar, fabsf(v));
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+    y2 += (double)v * (double)v;
+  }
+  ab = block_fmax_256(ab, red4);
+  ar = block_fmax_256(ar, red4);
+  mx = block_fmax_256(mx, red4);
+  mn = -block_fmax_256(-mn, red4);
+  const double y2t = block_sum_256(y2, shd);
+
+  float t = ar;
+  if (quant < 1.0) {
+    // order statistics k and k+1 (ascending) of |y| by a 4 x 8-bit radix select on the bit patterns
+    const double pos = quant * (double)(d - 1);
+    const int k = (int)floor(pos);
+    const float frac = (float)(pos - (double)k);
+    unsigned prefix = 0u, mask = 0u;
+    int kk = k;
+#pragma unroll 1
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      hist[tid] = 0u;
+      __syncthreads();
+      for (int j = tid; j < d; j += 256) {
+        const unsigned u = __float_as_uint(fabsf(row[j]));
+        if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        unsigned cum = 0u;
+        int b = 0;
+        for (; b < 255; ++b) {
+          if (cum + hist[b] > (unsigned)kk) break;
+          cum += hist[b];
+        }
+        sel[0] = (unsigned)b;
+        sel[1] = cum;
+      }
+      __syncthreads();
+      prefix |= sel[0] << shift;
+      kk -= (int)sel[1];
+      mask |= 255u << shift;
+      __syncthreads();
+    }
+    // prefix = bits of a_k; a_{k+1} = a_k if enough copies of it, else the smallest larger value
+    unsigned le = 0u, nxt = 0xffffffffu;
+    for (int j = tid; j < d; j += 256) {
+      const unsigned u = __float_as_uint(fabsf(row[j]));
+      if (u <= prefix) le += 1u;
+      else if (u < nxt) nxt = u;
+    }
+    const double le_t = block_sum_256((double)le, shd);
+    nxt = block_umin_256(nxt, ured4);
+    const float ak = __uint_as_float(prefix);
+    const float ak1 = ((int)le_t >= k + 2 || nxt == 0xffffffffu) ? ak : __uint_as_float(nxt);
+    float inc = __fmul_rn(frac, __fsub_rn(ak1, ak));
+    asm volatile("" : "+v"(inc));  // keep the product rounded: no contraction with the add below
+    t = __fadd_rn(ak, inc);
+  }
+  const float ss = __fdiv_rn(t, 7.0f);
+  const float rs = ss > 0.f ? __fdiv_rn(1.0f, ss) : 0.f;
+  const float sa = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+  const float ra = sa > 0.f ? __fdiv_rn(1.0f, sa) : 0.f;
+  double es = 0.0, ea = 0.0;
+  for (int j = tid; j < d; j += 256) {
+    const float v = row[j];
+    float q = rintf(__fmul_rn(v, rs));
+    q = fminf(fmaxf(q, -7.f), 7.f);
+    const double dsym = (double)v - (double)q * (double)ss;
+    es += dsym * dsym;
+    float qa = rintf(__fmul_rn(__fsub_rn(v, mn), ra));
+    qa = fminf(fmaxf(qa, 0.f), 15.f);
+    const double dasy = (double)v - ((double)qa * (double)sa + (double)mn);
+    ea += dasy * dasy;
+  }
+  const double est = block_sum_256(es, shd);
+  __syncthreads();
+  const double eat = block_sum_256(ea, shd);
+  if (tid == 0) {
+    const int64_t o = (int64_t)batch * n + token;
+    if (amax_out) { amax_out[2 * o] = ab; amax_out[2 * o + 1] = ar; }
+    if (thr_out) thr_out[o] = t;
+    if (err_sym) { err_sym[2 * o] = (float)est; err_sym[2 * o + 1] = (float)y2t; }
+    if (err_asym) { err_asym[2 * o] = (float)eat; err_asym[2 * o + 1] = (float)y2t; }
+    if (success && ar < ab) atomicAdd(&success[batch], 1ull);
+  }
+}
+
 }  // namespace kt
