@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
+    ap.add_argument("--op", choices=["step", "quant-metrics"], default="step",
+                    help="what a 'step' is: the training step (default, the headline metric) or one call of "
+                         "kt_rotate_quant_metrics (evaluation-side figures) on the same activations")
     ap.add_argument("--loss", choices=["row", "pooled"], default="row",
                     help="per-token-row kurtosis (default, the headline step) or the paper-literal pooled loss "
                          "with RMSNorm (kappa_target 1.8)")
@@ -95,6 +98,17 @@ def main():
         else:
             kt.kt_cayley_step(Rw, dR, lr, info=info, workspace=ws)
 
+    if args.op == "quant-metrics":
+        ws.get(kt.kt_workspace_bytes(kt.KT_OP_QUANT_METRICS, batch, n, d, kt.KT_BF16 if bf16 else kt.KT_F32))
+        q_amax = torch.empty((batch, n, 2), device=dev)
+        q_es = torch.empty((batch, n, 2), device=dev)
+        q_ea = torch.empty((batch, n, 2), device=dev)
+        q_succ = torch.zeros(batch, dtype=torch.int64, device=dev)
+
+        def step():  # noqa: F811
+            kt.kt_rotate_quant_metrics(X, Rw, quantile=0.98, amax=q_amax, err_sym=q_es, err_asym=q_ea,
+                                       success=q_succ, workspace=ws)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -107,8 +121,35 @@ def main():
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    prof = {k: kt.kt_profile_read(k) for k in range(5)}
+    prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
+    if args.op == "quant-metrics":
+        ms = 1e3 * elapsed / args.steps
+        esz = 2 if bf16 else 4
+        alg_bytes = batch * n * d * esz                 # the activations once: what the figures need
+        hw_bytes = batch * n * d * (2 * esz + 8)        # X twice (GEMM, baseline max), Y written and read (fp32)
+        flops_call = 2.0 * batch * n * d * d
+        peak_call = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+        print(json.dumps({
+            "metric": "tokens/sec through kt_rotate_quant_metrics (rotation GEMM + per-token row kernel)",
+            "value": round(batch * n * args.steps / elapsed, 1), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+            "config": {"workload": f"{args.config}: n={n} tokens x d={d}, batch={batch}, quantile 0.98"},
+            # d >= 2048: the rotation GEMM (2 n d^2 flop) bounds the call; below, the row kernel's HBM traffic
+            "roofline": ({"bound": "mfma", "kernel": "whole call (gemm_nt_kernel<EpiStore> + quant_metrics_row_kernel)",
+                          "achieved": round(flops_call / (ms * 1e-3) / 1e12, 1), "peak": peak_call, "unit": "TFLOP/s",
+                          "frac": round(flops_call / (ms * 1e-3) / 1e12 / peak_call, 4), "flops_per_launch": flops_call,
+                          "traffic": None} if d >= 2048 else
+                         {"bound": "hbm", "kernel": "whole call (gemm_nt_kernel<EpiStore> + quant_metrics_row_kernel)",
+                          "achieved": round(alg_bytes / (ms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                          "frac": round(alg_bytes / (ms * 1e-3) / 1e9 / 8000.0, 4), "bytes_per_launch": alg_bytes,
+                          "hardware_bytes": hw_bytes, "traffic": None}),
+            "success_rate": [float(x) / n for x in q_succ.cpu().tolist()[:4]],
+            "rel_err_sym_int4_q98": float(q_es[0, :, 0].double().sum() / q_es[0, :, 1].double().sum()),
+            "rel_err_asym_int4": float(q_ea[0, :, 0].double().sum() / q_ea[0, :, 1].double().sum()),
+            "cpu_baseline": None}))
+        return
 
     if args.pmc_calibration:
         Xc = torch.empty_like(X)

@@ -586,6 +586,16 @@ __device__ __forceinline__ float block_fmax_256(float v, float* red4) {
   __syncthreads();
   return fmaxf(fmaxf(red4[0], red4[1]), fmaxf(red4[2], red4[3]));
 }
+// Sum over the 256 threads in a fixed order (xor butterfly inside each wave, then the four wave
+// sums left to right): two barriers instead of the nine of the LDS tree.
+__device__ __forceinline__ double block_dsum_fast_256(double v, double* red4) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return ((red4[0] + red4[1]) + red4[2]) + red4[3];
+}
 __device__ __forceinline__ unsigned block_umin_256(unsigned v, unsigned* red4) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
@@ -611,7 +621,7 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
                                                                 unsigned long long* __restrict__ success) {
   extern __shared__ __align__(16) float row[];
   __shared__ unsigned hist[256];
-  __shared__ double shd[256];
+  __shared__ double shd[4];
   __shared__ float red4[4];
   __shared__ unsigned ured4[4];
   __shared__ unsigned sel[2];
@@ -633,7 +643,7 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
   ar = block_fmax_256(ar, red4);
   mx = block_fmax_256(mx, red4);
   mn = -block_fmax_256(-mn, red4);
-  const double y2t = block_sum_256(y2, shd);
+  const double y2t = block_dsum_fast_256(y2, shd);
 
   float t = ar;
   if (quant < 1.0) {
@@ -647,20 +657,43 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
     for (int shift = 24; shift >= 0; shift -= 8) {
       hist[tid] = 0u;
       __syncthreads();
+      // the high digits of a row's magnitudes fall into very few bins: count runs privately and
+      // touch the shared histogram only when the bin changes
+      unsigned run_bin = 0xffffffffu, run_cnt = 0u;
       for (int j = tid; j < d; j += 256) {
         const unsigned u = __float_as_uint(fabsf(row[j]));
-        if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-      if (tid == 0) {
-        unsigned cum = 0u;
-        int b = 0;
-        for (; b < 255; ++b) {
-          if (cum + hist[b] > (unsigned)kk) break;
-          cum += hist[b];
+        if ((u & mask) == prefix) {
+          const unsigned bin = (u >> shift) & 255u;
+          if (bin == run_bin) {
+            run_cnt += 1u;
+          } else {
+            if (run_cnt) atomicAdd(&hist[run_bin], run_cnt);
+            run_bin = bin;
+            run_cnt = 1u;
+          }
         }
-        sel[0] = (unsigned)b;
-        sel[1] = cum;
+      }
+      if (run_cnt) atomicAdd(&hist[run_bin], run_cnt);
+      __syncthreads();
+      if (tid < 64) {  // wave 0: lane l owns bins 4l .. 4l+3; prefix scan over the lanes
+        const unsigned c0 = hist[4 * tid], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
+        const unsigned own = c0 + c1 + c2 + c3;
+        unsigned incl = own;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const unsigned up = (unsigned)__shfl_up((int)incl, o);
+          if (tid >= o) incl += up;
+        }
+        const unsigned excl = incl - own;
+        if (excl <= (unsigned)kk && (unsigned)kk < incl) {  // exactly one lane (the counts sum to > kk)
+          unsigned cum = excl;
+          int b = 4 * tid;
+          if (cum + c0 <= (unsigned)kk) { cum += c0; ++b;
+            if (cum + c1 <= (unsigned)kk) { cum += c1; ++b;
+              if (cum + c2 <= (unsigned)kk) { cum += c2; ++b; } } }
+          sel[0] = (unsigned)b;
+          sel[1] = cum;
+        }
       }
       __syncthreads();
       prefix |= sel[0] << shift;
@@ -675,7 +708,7 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
       if (u <= prefix) le += 1u;
       else if (u < nxt) nxt = u;
     }
-    const double le_t = block_sum_256((double)le, shd);
+    const double le_t = block_dsum_fast_256((double)le, shd);
     nxt = block_umin_256(nxt, ured4);
     const float ak = __uint_as_float(prefix);
     const float ak1 = ((int)le_t >= k + 2 || nxt == 0xffffffffu) ? ak : __uint_as_float(nxt);
@@ -699,9 +732,8 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
     const double dasy = (double)v - ((double)qa * (double)sa + (double)mn);
     ea += dasy * dasy;
   }
-  const double est = block_sum_256(es, shd);
-  __syncthreads();
-  const double eat = block_sum_256(ea, shd);
+  const double est = block_dsum_fast_256(es, shd);
+  const double eat = block_dsum_fast_256(ea, shd);
   if (tid == 0) {
     const int64_t o = (int64_t)batch * n + token;
     if (amax_out) { amax_out[2 * o] = ab; amax_out[2 * o + 1] = ar; }
