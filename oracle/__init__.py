@@ -18,4 +18,6 @@ from .binding import (  # noqa: F401
     cayley_adam_step,
     fakequant_int4,
     quant_metrics,
+    hadamard_rows,
+    fuse_rotation,
 )

@@ -51,6 +51,10 @@ def _load():
     lib.kto_cayley_adam_step.restype = ctypes.c_int
     lib.kto_quant_metrics.argtypes = [dp, dp, fp, i64, i64, ctypes.c_double, fp, fp, dp, dp]
     lib.kto_quant_metrics.restype = ctypes.c_int64
+    lib.kto_hadamard_rows.argtypes = [dp, dp, i64, i64, dp]
+    lib.kto_hadamard_rows.restype = None
+    lib.kto_fuse_rotation.argtypes = [dp, dp, i64, i64, ctypes.c_int, dp]
+    lib.kto_fuse_rotation.restype = None
     lib.kto_fakequant_int4.argtypes = [dp, dp, i64, i64, ctypes.c_float, fp, fp, i8p, dp]
     lib.kto_fakequant_int4.restype = None
     _lib = lib
@@ -187,4 +191,26 @@ def quant_metrics(X, R, quantile=0.98, Y=None):
     succ = _load().kto_quant_metrics(_p(X), _p(R), _p(Yf, ctypes.c_float), n, d, float(quantile),
                                      _p(amax, ctypes.c_float), _p(thr, ctypes.c_float), _p(es), _p(ea))
     return {"success": int(succ), "amax": amax, "thr": thr, "err_sym": es, "err_asym": ea}
+
+
+def hadamard_rows(X, signs=None):
+    """Y = (X * signs) H_d / sqrt(d), rows of X; d a power of two."""
+    X = _d(X)
+    n, d = X.shape
+    assert d & (d - 1) == 0
+    sg = None if signs is None else _d(signs)
+    Y = np.empty((n, d), dtype=np.float64)
+    _load().kto_hadamard_rows(_p(X), _p(sg), n, d, _p(Y))
+    return Y
+
+
+def fuse_rotation(W, R, side):
+    """side 0: W [k][d] -> W R;  side 1: W [d][k] -> R^T W."""
+    W, R = _d(W), _d(R)
+    d = R.shape[0]
+    k = W.shape[0] if side == 0 else W.shape[1]
+    assert W.shape == ((k, d) if side == 0 else (d, k))
+    out = np.empty_like(W)
+    _load().kto_fuse_rotation(_p(W), _p(R), k, d, int(side), _p(out))
+    return out
 

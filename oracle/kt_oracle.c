@@ -52,6 +52,12 @@
  *                                          0.98), asymmetric int4 error (Background:
  *                                          b = min, s = (max - min)/(2^k - 1); Setup: KV)
  *
+ *   kto_hadamard_rows   the online rotations R3-R5 ("Placement of the Rotations": random
+ *                                          Hadamard matrices): y = (x * signs) H_d / sqrt(d) with
+ *                                          the Sylvester matrix H_2m = [[H_m, H_m], [H_m, -H_m]]
+ *   kto_fuse_rotation   merging a fusible rotation into a weight matrix ("Placement of
+ *                                          the Rotations"): W R or R^T W
+ *
  * Degenerate rows (no spread: m2 <= 1e-30 * mean(y^2), or an all-zero row):
  * kappa := 0, gradient row := 0, the row still counts in the 1/n.
  *
@@ -601,5 +607,50 @@ int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, i
   }
   if (Y) free(Y);
   return succ;
+}
+
+/*
+ * Y[i][:] = (X[i][:] * signs) H_d / sqrt(d), d a power of two, H_d the Sylvester-Hadamard matrix
+ * written out entry by entry: H[a][b] = (-1)^popcount(a & b)  (the closed form of the recursion
+ * H_1 = [1], H_2m = [[H_m, H_m], [H_m, -H_m]]).  signs (d values +-1) may be NULL.
+ * Plain O(d^2) per row: this is the definition, not a fast transform.
+ */
+void kto_hadamard_rows(const double *X, const double *signs, int64_t n, int64_t d, double *Y) {
+  const double sc = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) {
+    for (int64_t b = 0; b < d; ++b) {
+      double acc = 0.0;
+      for (int64_t a = 0; a < d; ++a) {
+        const double x = X[i * d + a] * (signs ? signs[a] : 1.0);
+        acc += (__builtin_popcountll((unsigned long long)(a & b)) & 1) ? -x : x;
+      }
+      Y[i * d + b] = acc * sc;
+    }
+  }
+}
+
+/*
+ * Fusing a rotation into a weight matrix: side = 0: Wout[k][d] = W[k][d] R[d][d]   (rotation on the
+ * right of the weight);  side = 1: Wout[d][k] = R^T[d][d] W[d][k]   (inverse rotation on its left).
+ */
+void kto_fuse_rotation(const double *W, const double *R, int64_t k, int64_t d, int side, double *Wout) {
+  if (side == 0) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < k; ++i)
+      for (int64_t j = 0; j < d; ++j) {
+        double acc = 0.0;
+        for (int64_t m = 0; m < d; ++m) acc += W[i * d + m] * R[m * d + j];
+        Wout[i * d + j] = acc;
+      }
+  } else {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < d; ++i)
+      for (int64_t j = 0; j < k; ++j) {
+        double acc = 0.0;
+        for (int64_t m = 0; m < d; ++m) acc += R[m * d + i] * W[m * k + j];
+        Wout[i * k + j] = acc;
+      }
+  }
 }
 
