@@ -226,6 +226,19 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The online rotations of "Placement of the Rotations" (R3, R4, R5: random Hadamard matrices
+ * applied to activations at run time):  Y[i][:] = (X[i][:] * signs) H_d / sqrt(d) for every
+ * token row, H_d the Sylvester-Hadamard matrix (H_1 = [1], H_2m = [[H_m, H_m], [H_m, -H_m]]).
+ *  X, Y   [n][ldx], [n][ldy] row-major, `dtype` (KT_BF16: fp32 arithmetic, rounded to nearest
+ *         even at the end); Y may be X (in place).  Rows 16-byte aligned.
+ *  signs  [d] int8 +-1 (the random diagonal of a "random Hadamard" rotation), or NULL.
+ *  d      power of two, 128 <= d <= 4096.  Without signs the transform is its own inverse.
+ * No workspace.  HBM-bound: one read and one write of the rows.
+ */
+kt_status kt_hadamard_rows(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs,
+                           int64_t n, int64_t d, kt_dtype dtype, void* stream);
+
+/*
  * Measurement aid (not part of the method; off by default).  When enabled, the
  * library brackets its large launches with HIP events on the caller's stream so a
  * benchmark can read per-kernel durations without a profiler attached.  This is the

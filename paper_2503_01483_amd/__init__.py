@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     kt_cayley_adam_step,
     kt_rotate_fakequant_int4,
     kt_rotate_quant_metrics,
+    kt_hadamard_rows,
     Workspace,
     kt_profile_enable,
     kt_profile_read,

@@ -12,7 +12,7 @@ KT_F32, KT_BF16 = 0, 1
 KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD, KT_OP_QUANT_METRICS = 0, 1, 2, 3, 4
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_profile_enable", "kt_profile_read",
+           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_profile_enable", "kt_profile_read",
            "kt_profile_reset")
 
 
@@ -52,6 +52,8 @@ def lib():
     L.kt_rotate_quant_metrics.restype = i32
     L.kt_rotate_quant_metrics.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp,
                                           vp, sz, vp]
+    L.kt_hadamard_rows.restype = i32
+    L.kt_hadamard_rows.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.kt_cayley_adam_step.restype = i32
@@ -213,6 +215,19 @@ def kt_rotate_quant_metrics(X, R, *, quantile=0.98, Y=None, amax=None, threshold
                                          _dtype_code(R), float(quantile), _ptr(Y), _ptr(amax), _ptr(threshold),
                                          _ptr(err_sym), _ptr(err_asym), _ptr(success), _ptr(ws), ws.numel(),
                                          _stream(stream)))
+
+
+def kt_hadamard_rows(X, *, signs=None, out=None, stream=None):
+    """Y = (X * signs) H_d / sqrt(d) on the rows of X [n][d] (fp32 or bf16); returns Y (out or new)."""
+    assert X.dim() == 2 and X.stride(1) == 1
+    n, d = X.shape
+    Y = torch.empty_like(X) if out is None else out
+    assert Y.shape == X.shape and Y.dtype == X.dtype and Y.stride(1) == 1
+    if signs is not None:
+        assert signs.dtype == torch.int8 and signs.numel() == d and signs.is_contiguous()
+    _check(lib().kt_hadamard_rows(_ptr(X), X.stride(0), _ptr(Y), Y.stride(0), _ptr(signs), n, d, _dtype_code(X),
+                                  _stream(stream)))
+    return Y
 
 
 def kt_profile_enable(max_records):

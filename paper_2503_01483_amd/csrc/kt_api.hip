@@ -10,6 +10,7 @@
 #include "kt_aux.h"
 #include "kt_cayley_d128.h"
 #include "kt_fused_d128.h"
+#include "kt_hadamard.h"
 
 namespace kt {
 
@@ -620,6 +621,40 @@ static kt_status cayley_run(const CayleyPlan& p, char* ws, float* R, const float
 }
 
 
+// ------------------------------------------------------------- Hadamard rows ----
+template <typename T, int LOG2D>
+static kt_status launch_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs, int64_t n,
+                                 hipStream_t st) {
+  constexpr size_t lds = 4 * (size_t)kHadRegion * 4;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_rows_kernel<T, LOG2D>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return fail(KT_ERR_DEVICE, "the Hadamard kernel needs %d bytes of LDS per workgroup", (int)lds);
+    attr_done = true;
+  }
+  const int64_t rows = kHadChunk >> LOG2D, chunks = ceil_div(n, rows);
+  const int64_t wgs = ceil_div(chunks, 4) < 2 * kNumCUs ? ceil_div(chunks, 4) : 2 * kNumCUs;
+  hipLaunchKernelGGL((hadamard_rows_kernel<T, LOG2D>), dim3((unsigned)wgs), dim3(256), lds, st,
+                     static_cast<const T*>(X), ldx, static_cast<T*>(Y), ldy, signs, n,
+                     1.0f / sqrtf((float)(1 << LOG2D)));
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "Hadamard launch failed");
+  return KT_OK;
+}
+
+template <typename T>
+static kt_status dispatch_hadamard(int log2d, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                                   const int8_t* signs, int64_t n, hipStream_t st) {
+  switch (log2d) {
+    case 7: return launch_hadamard<T, 7>(X, ldx, Y, ldy, signs, n, st);
+    case 8: return launch_hadamard<T, 8>(X, ldx, Y, ldy, signs, n, st);
+    case 9: return launch_hadamard<T, 9>(X, ldx, Y, ldy, signs, n, st);
+    case 10: return launch_hadamard<T, 10>(X, ldx, Y, ldy, signs, n, st);
+    case 11: return launch_hadamard<T, 11>(X, ldx, Y, ldy, signs, n, st);
+    default: return launch_hadamard<T, 12>(X, ldx, Y, ldy, signs, n, st);
+  }
+}
+
 extern "C" {
 
 int32_t kt_version(void) { return 100; }
@@ -836,6 +871,28 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
   if (fp32) return rotate(float{}, TF{});
   if (d % 256 == 0) return rotate(bf16{}, TB_BIG{});
   return rotate(bf16{}, TB_N128{});
+}
+
+kt_status kt_hadamard_rows(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs, int64_t n,
+                           int64_t d, kt_dtype dtype, void* stream) {
+  g_err[0] = 0;
+  if (!X || !Y) return fail(KT_ERR_INVALID_ARG, "X and Y must not be null");
+  if (n < 1) return fail(KT_ERR_INVALID_ARG, "n must be positive");
+  if (dtype != KT_F32 && dtype != KT_BF16) return fail(KT_ERR_BAD_DTYPE, "dtype must be KT_F32 or KT_BF16");
+  if (d < 128 || d > 4096 || (d & (d - 1)) != 0)
+    return fail(KT_ERR_BAD_SHAPE, "d = %lld: the Hadamard transform here needs a power of two in [128, 4096]",
+                (long long)d);
+  const int64_t vec = dtype == KT_F32 ? 4 : 8;
+  if (ldx < d || ldy < d || ldx % vec != 0 || ldy % vec != 0)
+    return fail(KT_ERR_BAD_SHAPE, "ldx / ldy must be >= d and keep rows 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Y)) & 15)
+    return fail(KT_ERR_BAD_SHAPE, "X and Y must be 16-byte aligned");
+  int log2d = 0;
+  while ((int64_t(1) << log2d) < d) ++log2d;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ProfScope prof(5, st);
+  if (dtype == KT_F32) return dispatch_hadamard<float>(log2d, X, ldx, Y, ldy, signs, n, st);
+  return dispatch_hadamard<bf16>(log2d, X, ldx, Y, ldy, signs, n, st);
 }
 
 kt_status kt_profile_reset(void) {

@@ -1,0 +1,52 @@
+"""GPU parity of kt_hadamard_rows against the oracle's O(d^2) definition.
+fp32: the transform adds d values with fp32 rounding in a tree of depth log2 d: 1e-5 of the row
+norm per output.  bf16: the same fp32 result rounded to nearest even: at most one bf16 ulp
+(2^-8 relative) from the oracle value rounded the same way, plus the fp32 term."""
+import numpy as np
+import pytest
+import torch
+
+import ktgen
+import oracle
+import paper_2503_01483_amd as kt
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n,d,dtype,use_signs", [(37, 128, "f32", False), (1000, 128, "bf16", True), (33, 256, "f32", True),
+                                                  (515, 512, "bf16", False), (70, 1024, "f32", True), (9, 2048, "bf16", True),
+                                                  (130, 4096, "bf16", False), (5, 4096, "f32", True)])
+def test_against_oracle(n, d, dtype, use_signs):
+    X = ktgen.make_x(n, d, seed=n + d, outlier_cols=3, outlier_scale=40.0, t_frac=0.02, dtype=dtype)
+    g = torch.Generator().manual_seed(d)
+    signs = (torch.randint(0, 2, (d,), generator=g) * 2 - 1).to(torch.int8) if use_signs else None
+    Y = kt.kt_hadamard_rows(X.cuda(), signs=None if signs is None else signs.cuda())
+    torch.cuda.synchronize()
+    ref = oracle.hadamard_rows(ktgen.to_f64(X), None if signs is None else signs.numpy().astype(np.float64))
+    got = Y.float().cpu().numpy().astype(np.float64)
+    rown = np.linalg.norm(ref, axis=1, keepdims=True)
+    tol = 1e-5 * rown + (np.abs(ref) * 2.0 ** -8 if dtype == "bf16" else 0.0)
+    assert (np.abs(got - ref) <= tol).all(), float((np.abs(got - ref) / rown).max())
+
+
+def test_in_place_strided_and_involution():
+    n, d = 300, 256
+    buf = torch.randn(n, d + 64, device="cuda")
+    X = buf[:, :d]                                   # row stride d + 64
+    ref = oracle.hadamard_rows(X.cpu().numpy().astype(np.float64))
+    guard = buf[:, d:].clone()
+    kt.kt_hadamard_rows(X, out=X)
+    torch.cuda.synchronize()
+    assert np.abs(X.cpu().numpy() - ref).max() < 1e-4
+    assert torch.equal(buf[:, d:], guard)            # nothing written past the d columns
+    kt.kt_hadamard_rows(X, out=X)                    # H/sqrt(d) is its own inverse
+    torch.cuda.synchronize()
+    assert np.abs(oracle.hadamard_rows(ref) - X.cpu().numpy()).max() < 1e-4
+
+
+def test_bad_shapes_are_refused():
+    X = torch.zeros(4, 96, device="cuda")
+    with pytest.raises(Exception):
+        kt.kt_hadamard_rows(X)
+    with pytest.raises(Exception):
+        kt.kt_hadamard_rows(torch.zeros(4, 8192, device="cuda"))
