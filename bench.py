@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
-    ap.add_argument("--op", choices=["step", "quant-metrics"], default="step",
+    ap.add_argument("--op", choices=["step", "quant-metrics", "hadamard"], default="step",
                     help="what a 'step' is: the training step (default, the headline metric) or one call of "
                          "kt_rotate_quant_metrics (evaluation-side figures) on the same activations")
     ap.add_argument("--loss", choices=["row", "pooled"], default="row",
@@ -109,6 +109,13 @@ def main():
             kt.kt_rotate_quant_metrics(X, Rw, quantile=0.98, amax=q_amax, err_sym=q_es, err_asym=q_ea,
                                        success=q_succ, workspace=ws)
 
+    if args.op == "hadamard":
+        Xh = X.reshape(batch * n, d)
+        Yh = torch.empty_like(Xh)
+
+        def step():  # noqa: F811
+            kt.kt_hadamard_rows(Xh, out=Yh)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -123,6 +130,20 @@ def main():
     elapsed = time.perf_counter() - t0
     prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
+    if args.op == "hadamard":
+        ms = 1e3 * elapsed / args.steps
+        nbytes = 2.0 * batch * n * d * (2 if bf16 else 4)     # rows read once, written once
+        print(json.dumps({
+            "metric": "tokens/sec through kt_hadamard_rows (online Hadamard rotation of token rows)",
+            "value": round(batch * n * args.steps / elapsed, 1), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+            "config": {"workload": f"{args.config}: {batch * n} token rows x d={d}"},
+            "roofline": {"bound": "hbm", "kernel": "hadamard_rows_kernel", "achieved": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                         "peak": 8000.0, "unit": "GB/s", "frac": round(nbytes / (ms * 1e-3) / 1e9 / 8000.0, 4),
+                         "bytes_per_launch": nbytes, "traffic": None},
+            "cpu_baseline": None}))
+        return
     if args.op == "quant-metrics":
         ms = 1e3 * elapsed / args.steps
         esz = 2 if bf16 else 4

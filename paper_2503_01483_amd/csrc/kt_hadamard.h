@@ -4,7 +4,8 @@
 //
 // HBM-bound: 2 d element reads + 2 d element writes per row against d log2 d additions.  One WAVE
 // owns a chunk of 4096 consecutive elements (4096 / d whole rows) and never meets the other waves:
-//   1. coalesced 16-byte global loads -> fp32 -> its private LDS region (linear order)
+//   1. coalesced 16-byte global loads (issued one chunk ahead) -> fp32 -> its private LDS
+//      region (linear order)
 //   2. each lane takes 64 consecutive elements: six butterfly stages in registers
 //   3. through LDS again, transposed: each lane now holds the elements 64 apart, i.e. the
 //      remaining log2(d) - 6 index bits of a row: the last stages in registers
@@ -53,9 +54,27 @@ __global__ __launch_bounds__(256) void hadamard_rows_kernel(const T* __restrict_
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float* lds = lds_all + wave * kHadRegion;
   const int64_t chunks = (n + ROWS - 1) / ROWS;
-  for (int64_t chunk = (int64_t)blockIdx.x * 4 + wave; chunk < chunks; chunk += (int64_t)gridDim.x * 4) {
+  // the loads of the next chunk are in flight while this one is transformed
+  intx4 nxt[NLD];
+  auto request = [&](int64_t chunk) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < NLD; ++t) {
+      const int i = (t * 64 + lane) * VEC;
+      const int64_t row = chunk * ROWS + (i >> LOG2D);
+      intx4 r = {0, 0, 0, 0};
+      if (chunk < chunks && row < n) r = *reinterpret_cast<const intx4*>(X + row * ldx + (i & (D - 1)));
+      nxt[t] = r;
+    }
+  };
+  const int64_t stride = (int64_t)gridDim.x * 4;
+  request((int64_t)blockIdx.x * 4 + wave);
+  for (int64_t chunk = (int64_t)blockIdx.x * 4 + wave; chunk < chunks; chunk += stride) {
     const int64_t row0 = chunk * ROWS;
-    // 1. global -> LDS (linear, padded)
+    intx4 cur[NLD];
+#pragma unroll
+    for (int t = 0; t < NLD; ++t) cur[t] = nxt[t];
+    request(chunk + stride);
+    // 1. registers -> LDS (linear, padded)
 #pragma unroll
     for (int t = 0; t < NLD; ++t) {
       const int i = (t * 64 + lane) * VEC;
@@ -63,7 +82,7 @@ __global__ __launch_bounds__(256) void hadamard_rows_kernel(const T* __restrict_
       const int col = i & (D - 1);
       float v[VEC];
       if (row < n) {
-        const intx4 raw = *reinterpret_cast<const intx4*>(X + row * ldx + col);
+        const intx4 raw = cur[t];
         if constexpr (sizeof(T) == 4) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = __int_as_float(raw[e]);
