@@ -51,7 +51,7 @@ enum {
 
 typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
 typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3,
-               KT_OP_QUANT_METRICS = 4 } kt_op;
+               KT_OP_QUANT_METRICS = 4, KT_OP_FUSE_ROTATION = 5 } kt_op;
 
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
@@ -237,6 +237,21 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
  */
 kt_status kt_hadamard_rows(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs,
                            int64_t n, int64_t d, kt_dtype dtype, void* stream);
+
+/*
+ * Merging a fusible rotation (R1, R2 of "Placement of the Rotations") into a weight matrix, in
+ * fp32:
+ *   side 0:  Wout [k][d] = W [k][d] R          (the rotation on the right of a weight that writes
+ *                                               the rotated stream: embedding, W_o, W_down, W_v)
+ *   side 1:  Wout [d][k] = R^T W [d][k]        (its inverse on the left of a weight that reads it:
+ *                                               W_q, W_k, W_v, W_up, W_gate; W_o for R2)
+ * with x W for row-vector activations x.  W, R, Wout fp32 row-major with leading dimensions ldw,
+ * ldr, ldo (multiples of 4); d multiple of 128; Wout must not overlap W.
+ * Workspace: kt_workspace_bytes(KT_OP_FUSE_ROTATION, 1, k, d, KT_F32)  (n = k).
+ */
+kt_status kt_fuse_rotation(const float* W, int64_t ldw, const float* R, int64_t ldr, float* Wout,
+                           int64_t ldo, int64_t k, int64_t d, int32_t side,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid (not part of the method; off by default).  When enabled, the

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     KT_OP_FAKEQUANT,
     KT_OP_POOLED_LOSS_GRAD,
     KT_OP_QUANT_METRICS,
+    KT_OP_FUSE_ROTATION,
     KtError,
     lib,
     lib_path,
@@ -26,6 +27,7 @@ from .binding import (  # noqa: F401
     kt_rotate_fakequant_int4,
     kt_rotate_quant_metrics,
     kt_hadamard_rows,
+    kt_fuse_rotation,
     Workspace,
     kt_profile_enable,
     kt_profile_read,

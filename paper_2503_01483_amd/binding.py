@@ -10,9 +10,10 @@ _lib = None
 
 KT_F32, KT_BF16 = 0, 1
 KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD, KT_OP_QUANT_METRICS = 0, 1, 2, 3, 4
+KT_OP_FUSE_ROTATION = 5
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_profile_enable", "kt_profile_read",
+           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_fuse_rotation", "kt_profile_enable", "kt_profile_read",
            "kt_profile_reset")
 
 
@@ -54,6 +55,8 @@ def lib():
                                           vp, sz, vp]
     L.kt_hadamard_rows.restype = i32
     L.kt_hadamard_rows.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, vp]
+    L.kt_fuse_rotation.restype = i32
+    L.kt_fuse_rotation.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i32, vp, sz, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.kt_cayley_adam_step.restype = i32
@@ -228,6 +231,19 @@ def kt_hadamard_rows(X, *, signs=None, out=None, stream=None):
     _check(lib().kt_hadamard_rows(_ptr(X), X.stride(0), _ptr(Y), Y.stride(0), _ptr(signs), n, d, _dtype_code(X),
                                   _stream(stream)))
     return Y
+
+
+def kt_fuse_rotation(W, R, side, *, out=None, workspace=None, stream=None):
+    """side 0: W [k][d] -> W R;  side 1: W [d][k] -> R^T W  (fp32)."""
+    d = R.shape[-1]
+    k = W.shape[0] if side == 0 else W.shape[1]
+    assert W.dtype == R.dtype == torch.float32 and W.stride(1) == 1 and R.stride(-1) == 1 and R.dim() == 2
+    out = torch.empty_like(W) if out is None else out
+    need = kt_workspace_bytes(KT_OP_FUSE_ROTATION, 1, k, d, KT_F32)
+    ws = (workspace or Workspace(W.device)).get(need)
+    _check(lib().kt_fuse_rotation(_ptr(W), W.stride(0), _ptr(R), R.stride(0), _ptr(out), out.stride(0), k, d,
+                                  int(side), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
 
 
 def kt_profile_enable(max_records):

@@ -674,6 +674,9 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
     case KT_OP_QUANT_METRICS:
       if (n < 1) return 0;
       return round_up(batch * d * d * (x_dtype == KT_F32 ? 4 : 2), 256) + (size_t)batch * n * d * 4;
+    case KT_OP_FUSE_ROTATION:  // n = the other dimension k of the weight
+      if (n < 1) return 0;
+      return round_up(d * d * 4, 256) + (size_t)n * d * 4;
     case KT_OP_CAYLEY:
       return plan_cayley(batch, d).total;
     case KT_OP_FAKEQUANT:
@@ -893,6 +896,45 @@ kt_status kt_hadamard_rows(const void* X, int64_t ldx, void* Y, int64_t ldy, con
   ProfScope prof(5, st);
   if (dtype == KT_F32) return dispatch_hadamard<float>(log2d, X, ldx, Y, ldy, signs, n, st);
   return dispatch_hadamard<bf16>(log2d, X, ldx, Y, ldy, signs, n, st);
+}
+
+kt_status kt_fuse_rotation(const float* W, int64_t ldw, const float* R, int64_t ldr, float* Wout, int64_t ldo,
+                           int64_t k, int64_t d, int32_t side, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  g_err[0] = 0;
+  if (!W || !R || !Wout) return fail(KT_ERR_INVALID_ARG, "W, R and Wout must not be null");
+  if (k < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "k and d must be positive");
+  if (side != 0 && side != 1) return fail(KT_ERR_INVALID_ARG, "side must be 0 (W R) or 1 (R^T W)");
+  if (d % 128 != 0 || d > 32768) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128 (<= 32768)", (long long)d);
+  if (k > (int64_t(1) << 22)) return fail(KT_ERR_BAD_SHAPE, "k out of range");
+  const int64_t wcols = side == 0 ? d : k;
+  if (ldw < wcols || ldo < wcols || ldr < d || ldw % 4 != 0 || ldo % 4 != 0 || ldr % 4 != 0)
+    return fail(KT_ERR_BAD_SHAPE, "leading dimensions must cover the rows and keep them 16-byte aligned");
+  if (side == 1 && k % 4 != 0) return fail(KT_ERR_BAD_SHAPE, "k must be a multiple of 4 for side 1");
+  const size_t rt_bytes = (size_t)round_up(d * d * 4, 256);
+  kt_status s = check_ws(workspace, workspace_bytes, rt_bytes + (side == 1 ? (size_t)k * d * 4 : 0));
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* RT = reinterpret_cast<float*>(ws);
+  if (!prep_rt<float>(R, ldr, KT_F32, RT, 1, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
+  ProfScope prof(5, st);
+  EpiStore<TF> e;
+  e.C = Wout; e.ldc = ldo; e.batch_stride = 0; e.split_stride = 0;
+  if (side == 0) {  // Wout [k][d] = W R = W (R^T)^T
+    e.M = (int)k; e.N = (int)d;
+    if (!launch_gemm<TF>(W, ldw, 0, (int)k, RT, d, 0, (int)d, d, 0, 1, e, st))
+      return fail(KT_ERR_DEVICE, "fusion GEMM launch failed");
+  } else {          // Wout [d][k] = R^T W = R^T (W^T)^T
+    float* Wt = reinterpret_cast<float*>(ws + rt_bytes);
+    hipLaunchKernelGGL(transpose_f32_kernel, dim3((unsigned)ceil_div(k, 32), (unsigned)ceil_div(d, 32)), dim3(256),
+                       0, st, W, ldw, Wt, d, (int)d, (int)k);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "weight transpose launch failed");
+    e.M = (int)d; e.N = (int)k;
+    if (!launch_gemm<TF>(RT, d, 0, (int)d, Wt, d, 0, (int)k, d, 0, 1, e, st))
+      return fail(KT_ERR_DEVICE, "fusion GEMM launch failed");
+  }
+  return KT_OK;
 }
 
 kt_status kt_profile_reset(void) {

@@ -744,4 +744,25 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
   }
 }
 
+// Plain fp32 matrix transpose out[c][r] = in[r][c] (rows x cols -> cols x rows), 32 x 32 tiles
+// through LDS; grid = (ceil(cols/32), ceil(rows/32)).
+__global__ __launch_bounds__(256) void transpose_f32_kernel(const float* __restrict__ in, int64_t ld_in,
+                                                            float* __restrict__ out, int64_t ld_out,
+                                                            int rows, int cols) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int r = r0 + ty + 8 * k, c = c0 + tx;
+    tile[ty + 8 * k][tx] = (r < rows && c < cols) ? in[(int64_t)r * ld_in + c] : 0.f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int c = c0 + ty + 8 * k, r = r0 + tx;
+    if (c < cols && r < rows) out[(int64_t)c * ld_out + r] = tile[tx][ty + 8 * k];
+  }
+}
+
 }  // namespace kt
