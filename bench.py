@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
-    ap.add_argument("--op", choices=["step", "quant-metrics", "hadamard"], default="step",
+    ap.add_argument("--op", choices=["step", "fakequant", "quant-metrics", "hadamard"], default="step",
                     help="what a 'step' is: the training step (default, the headline metric) or one call of "
                          "kt_rotate_quant_metrics (evaluation-side figures) on the same activations")
     ap.add_argument("--loss", choices=["row", "pooled"], default="row",
@@ -109,6 +109,16 @@ def main():
             kt.kt_rotate_quant_metrics(X, Rw, quantile=0.98, amax=q_amax, err_sym=q_es, err_asym=q_ea,
                                        success=q_succ, workspace=ws)
 
+    if args.op == "fakequant":
+        ws.get(kt.kt_workspace_bytes(kt.KT_OP_FAKEQUANT, batch, n, d, kt.KT_BF16 if bf16 else kt.KT_F32))
+        fq_codes = torch.empty((batch, n, d), dtype=torch.int8, device=dev)
+        fq_scales = torch.empty((batch, n), device=dev)
+        fq_err = torch.empty((batch, n, 2), device=dev)
+
+        def step():  # noqa: F811
+            kt.kt_rotate_fakequant_int4(X, Rw, clip_ratio=1.0, scales_out=fq_scales, codes=fq_codes, err=fq_err,
+                                        workspace=ws)
+
     if args.op == "hadamard":
         Xh = X.reshape(batch * n, d)
         Yh = torch.empty_like(Xh)
@@ -130,6 +140,23 @@ def main():
     elapsed = time.perf_counter() - t0
     prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
+    if args.op == "fakequant":
+        ms = 1e3 * elapsed / args.steps
+        flops_call = 4.0 * batch * n * d * d      # two GEMM passes: row maxima, then quantise the recomputed y
+        peak_call = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+        print(json.dumps({
+            "metric": "tokens/sec through kt_rotate_fakequant_int4 (rotate + per-token symmetric int4 codes, scales, error)",
+            "value": round(batch * n * args.steps / elapsed, 1), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+            "config": {"workload": f"{args.config}: n={n} tokens x d={d}, batch={batch}, clip 1.0, codes + scales + error"},
+            "roofline": {"bound": "mfma", "kernel": "whole call (gemm_nt_kernel<EpiAmax> + gemm_nt_kernel<EpiQuant>)",
+                         "achieved": round(flops_call / (ms * 1e-3) / 1e12, 1), "peak": peak_call, "unit": "TFLOP/s",
+                         "frac": round(flops_call / (ms * 1e-3) / 1e12 / peak_call, 4), "flops_per_launch": flops_call,
+                         "traffic": None},
+            "rel_err_int4": float(fq_err[0, :, 0].double().sum() / fq_err[0, :, 1].double().sum()),
+            "cpu_baseline": None}))
+        return
     if args.op == "hadamard":
         ms = 1e3 * elapsed / args.steps
         nbytes = 2.0 * batch * n * d * (2 if bf16 else 4)     # rows read once, written once

@@ -249,7 +249,7 @@ static QuantPlan plan_quant(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
   p.o_rt = c.take((size_t)batch * d * d * p.esz);
   p.o_amax = c.take((size_t)batch * p.P * n * 4);
   p.o_scales = c.take((size_t)batch * n * 4);
-  p.o_errpart = c.take((size_t)batch * p.PN * n * 8);
+  p.o_errpart = c.take((size_t)batch * p.P * n * 8);
   p.total = c.off;
   return p;
 }
@@ -464,15 +464,15 @@ static kt_status run_quant(const QuantPlan& p, const void* X, int64_t ldx, const
   }
   if (!codes && !err) return KT_OK;
   {
-    EpiQuant<TQ> e;
+    EpiQuant<TFWD> e;
     e.scales = scales; e.codes = codes; e.err_part = err ? errpart : nullptr;
-    e.n_tokens = (int)n; e.d = (int)d; e.PN = p.PN;
-    if (!launch_gemm<TQ>(Xp, ldx, n * ldx, (int)n, RT, d, d * d, (int)d, d, 0, (int)batch, e, st))
+    e.n_tokens = (int)n; e.d = (int)d; e.P = p.P;
+    if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
       return fail(KT_ERR_DEVICE, "quantise GEMM launch failed");
   }
   if (err) {
     hipLaunchKernelGGL(quant_err_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)batch), dim3(256), 0,
-                       st, errpart, p.PN, n, reinterpret_cast<float2*>(err));
+                       st, errpart, p.P, n, reinterpret_cast<float2*>(err));
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "error reduce launch failed");
   }
   return KT_OK;
@@ -814,6 +814,7 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
   if (!(clip_ratio > 0.f && clip_ratio <= 1.f))
     return fail(KT_ERR_INVALID_ARG, "clip_ratio must be in (0, 1]");
   if (!scales_out && !codes && !err) return fail(KT_ERR_INVALID_ARG, "no output requested");
+  if (reinterpret_cast<uintptr_t>(codes) & 3) return fail(KT_ERR_BAD_SHAPE, "codes must be 4-byte aligned");
   const QuantPlan p = plan_quant(batch, n, d, x_dtype);
   s = check_ws(workspace, workspace_bytes, p.total);
   if (s != KT_OK) return s;

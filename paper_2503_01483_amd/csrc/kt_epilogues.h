@@ -305,52 +305,55 @@ struct EpiAmax : EpiBase {
 };
 
 // ---- fake-quant pass B: quantise the recomputed y ----------------------------------
-// Orientation swapped: m = token, n = feature, so a lane group writes 32 consecutive
-// code bytes of one token.  q = clamp(rint(y * (1/s)), -7, 7) in fp32; per-token error
-// sums are reduced over the 32 feature lanes and stored per wave-column
-// pe[(batch*PN + pn)*n_tokens + token] = {sum (y - q s)^2, sum y^2}.
+// Same orientation as the moment epilogue (token on the lane, features on the registers): the
+// scale and its reciprocal are taken once per token, the error sums accumulate in registers and
+// meet only the other half-wave, and the four consecutive features a lane owns per register
+// group leave as one 4-byte store of packed codes.  q = clamp(rint(y * (1/s)), -7, 7) in fp32;
+// pe[(batch*P + p)*n_tokens + token] = {sum (y - q s)^2, sum y^2} over the wave's feature rows.
 template <class TL>
 struct EpiQuant : EpiBase {
   const float* scales;  // [batch][n_tokens]
   int8_t* codes;        // [batch][n_tokens][d] or null
   float2* err_part;     // or null
-  int n_tokens, d, PN;
-  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
-                                             int tn, int, int m0, int n0) const {
+  int n_tokens, d, P;
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int tm,
+                                             int, int, int m0, int n0) const {
     const Frag<TL> f;
-    const int pn = tn * TL::WGN + f.wn;
+    const int p = tm * TL::WGM + f.wm;
 #pragma unroll
-    for (int mb = 0; mb < TL::MB; ++mb) {
+    for (int nb = 0; nb < TL::NB; ++nb) {
+      const int token = n0 + f.n_of(nb);
+      const bool tv = token < n_tokens;
+      const float s = tv ? scales[(int64_t)batch * n_tokens + token] : 0.f;
+      const bool live = s > 0.f;
+      const float rinv = live ? __fdiv_rn(1.0f, s) : 0.f;
+      int8_t* crow = codes + ((int64_t)batch * n_tokens + token) * d;
+      float e2 = 0.f, y2 = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int token = m0 + f.m_of(mb, r);
-        const bool tv = token < n_tokens;
-        const float s = tv ? scales[(int64_t)batch * n_tokens + token] : 0.f;
-        const float rinv = s > 0.f ? __fdiv_rn(1.0f, s) : 0.f;
-        float e2 = 0.f, y2 = 0.f;
+      for (int mb = 0; mb < TL::MB; ++mb) {
+        if (m0 + f.m_block(mb) < d) {
 #pragma unroll
-        for (int nb = 0; nb < TL::NB; ++nb) {
-          const int feat = n0 + f.n_of(nb);
-          if (feat < d) {
-            const float y = acc[mb][nb][r];
-            float q = rintf(__fmul_rn(y, rinv));
-            q = fminf(fmaxf(q, -7.f), 7.f);
-            if (!(s > 0.f)) q = 0.f;
-            const float diff = y - q * s;
-            e2 = fmaf(diff, diff, e2);
-            y2 = fmaf(y, y, y2);
-            if (codes && tv) codes[((int64_t)batch * n_tokens + token) * d + feat] = (int8_t)q;
+          for (int g = 0; g < 4; ++g) {
+            unsigned pack = 0u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float y = acc[mb][nb][4 * g + e];
+              float q = rintf(__fmul_rn(y, rinv));
+              q = fminf(fmaxf(q, -7.f), 7.f);
+              if (!live) q = 0.f;
+              const float diff = y - q * s;
+              e2 = fmaf(diff, diff, e2);
+              y2 = fmaf(y, y, y2);
+              pack |= ((unsigned)(int)q & 0xffu) << (8 * e);
+            }
+            if (codes && tv) *reinterpret_cast<unsigned*>(crow + m0 + f.m_of(mb, 4 * g)) = pack;
           }
         }
-        if (err_part) {
-#pragma unroll
-          for (int o = 16; o >= 1; o >>= 1) {
-            e2 += __shfl_xor(e2, o);
-            y2 += __shfl_xor(y2, o);
-          }
-          if ((f.lane & 31) == 0 && tv)
-            err_part[((int64_t)batch * PN + pn) * n_tokens + token] = make_float2(e2, y2);
-        }
+      }
+      if (err_part) {
+        e2 += __shfl_xor(e2, 32);
+        y2 += __shfl_xor(y2, 32);
+        if (f.half == 0 && tv) err_part[((int64_t)batch * P + p) * n_tokens + token] = make_float2(e2, y2);
       }
     }
   }
