@@ -130,7 +130,9 @@ kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R
  *
  * The solve is the fixed-point iteration Z <- R - (lr/2) A (R + Z), run on the
  * device until successive iterates agree to the resolution of the arithmetic (max |dZ|
- * <= 3e-7, or <= 2e-5 and no longer shrinking); it contracts when (lr/2)||A||_2 < 1 and
+ * <= 3e-7; or <= 2e-5 and no longer shrinking; or, the iteration being linear, as soon as
+ * the observed contraction rho = |dZ_k| / |dZ_k-1| < 1/4 bounds the distance to the fixed
+ * point, 4 |dZ_k| rho, by 3e-7); it contracts when (lr/2)||A||_2 < 1 and
  * the library enqueues at most 32 iterations (enough up to about 0.6).  No learning-rate
  * clamp is applied: the caller chooses lr.  For d >= 1024 the d^3 products run on the
  * bf16 matrix cores as three-term bf16 products (about 2^-17 relative per term).

@@ -463,7 +463,7 @@ __global__ __launch_bounds__(256) void cayley_update_kernel(const float* __restr
   __shared__ unsigned sh[4];
   unsigned* dl = delta + (int64_t)blockIdx.y * max_iters;
   if (it > 0 && cayley_converged(dl, it - 1, tol)) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) dl[it] = dl[it - 1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) dl[it] = 0u;  // a zero change: later launches return too
     return;
   }
   const int64_t dd = (int64_t)d * d, bo = (int64_t)blockIdx.y * dd;

@@ -220,8 +220,7 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
         }
     dmax = c128_block_umax(dmax, red, wave, lane);  // its barrier also ends every wave's reads of bufA
     const float d1 = __uint_as_float(dmax);
-    // same rule as the generic path: below the tolerance, or stagnating on the rounding floor
-    const bool conv = d1 <= tol || (it > 0 && d1 <= 64.f * tol && d1 >= 0.9f * dprev);
+    const bool conv = cayley_converged_pair(d1, dprev, it > 0, tol);  // same rule as the generic path
     dprev = d1;
     if (conv) {
       used = it + 1;

@@ -173,11 +173,22 @@ __device__ __forceinline__ unsigned wave_umax(unsigned v) {
 // small (within 64 tolerances) and has stopped shrinking (>= 0.9 of the previous one):
 // the iterate then sits on the rounding floor of the arithmetic, which for the three-term
 // bf16 products lies at a few 1e-7 and would never pass a fixed fp32-sized tolerance.
-__device__ __forceinline__ bool cayley_converged(const unsigned* dl, int k, float tol) {
-  const float d1 = __uint_as_float(dl[k]);
+// One rule for every path: d1 = delta of iteration k, d0 = delta of iteration k-1.
+//  - below the tolerance; or
+//  - the iteration is linear and contracts geometrically, so after a step that shrank the change by
+//    rho = d1/d0 < 1/4 the iterate just written is within d1 rho/(1 - rho) of the fixed point: accept
+//    it when four times that bound is below the tolerance (saves the product that would only
+//    confirm it); or
+//  - small (within 64 tolerances) and no longer shrinking: the rounding floor of the arithmetic.
+__device__ __forceinline__ bool cayley_converged_pair(float d1, float d0, bool have_prev, float tol) {
   if (d1 <= tol) return true;
-  if (k == 0 || !(d1 <= 64.f * tol)) return false;
-  return d1 >= 0.9f * __uint_as_float(dl[k - 1]);
+  if (!have_prev) return false;
+  if (d1 < 0.25f * d0 && 4.f * d1 * (d1 / d0) <= tol) return true;
+  if (!(d1 <= 64.f * tol)) return false;
+  return d1 >= 0.9f * d0;
+}
+__device__ __forceinline__ bool cayley_converged(const unsigned* dl, int k, float tol) {
+  return cayley_converged_pair(__uint_as_float(dl[k]), k > 0 ? __uint_as_float(dl[k - 1]) : 0.f, k > 0, tol);
 }
 
 // Unew is written as fp32, or (Usplit != null) as the [hi | hi | lo] bf16 operand of the
@@ -196,8 +207,8 @@ struct EpiCayleyIter {
     if (it == 0) return false;
     const unsigned* dl = delta + (int64_t)batch * max_iters;
     if (!cayley_converged(dl, it - 1, tol)) return false;
-    // converged earlier: hand the small delta on so that later launches return too
-    if (blockIdx.x == 0 && threadIdx.x == 0) delta[(int64_t)batch * max_iters + it] = dl[it - 1];
+    // converged earlier: record a zero change so that every later launch returns too
+    if (blockIdx.x == 0 && threadIdx.x == 0) delta[(int64_t)batch * max_iters + it] = 0u;
     return true;
   }
   __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
