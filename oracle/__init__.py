@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     cayley_adam_step,
     fakequant_int4,
     quant_metrics,
+    quant_sensitivity,
     hadamard_rows,
     fuse_rotation,
 )

@@ -55,6 +55,8 @@ def _load():
     lib.kto_hadamard_rows.restype = None
     lib.kto_fuse_rotation.argtypes = [dp, dp, i64, i64, ctypes.c_int, dp]
     lib.kto_fuse_rotation.restype = None
+    lib.kto_quant_sensitivity.argtypes = [fp, i64, ctypes.c_int, fp, ctypes.c_int, dp, dp]
+    lib.kto_quant_sensitivity.restype = None
     lib.kto_fakequant_int4.argtypes = [dp, dp, i64, i64, ctypes.c_float, fp, fp, i8p, dp]
     lib.kto_fakequant_int4.restype = None
     _lib = lib
@@ -213,4 +215,16 @@ def fuse_rotation(W, R, side):
     out = np.empty_like(W)
     _load().kto_fuse_rotation(_p(W), _p(R), k, d, int(side), _p(out))
     return out
+
+
+def quant_sensitivity(y, alphas, bits=4):
+    """Optimal step of a symmetric `bits`-bit quantiser over all of y (float32) and the sensitivity
+    Gamma at the step fractions `alphas`.  Returns dict(s_opt, mse_opt, gamma float64[len(alphas)])."""
+    yf = np.ascontiguousarray(np.asarray(y, dtype=np.float32)).ravel()
+    al = np.ascontiguousarray(np.asarray(alphas, dtype=np.float32))
+    out = np.empty(2, dtype=np.float64)
+    gam = np.empty(al.size, dtype=np.float64)
+    _load().kto_quant_sensitivity(_p(yf, ctypes.c_float), yf.size, int(bits), _p(al, ctypes.c_float), al.size,
+                                  _p(out), _p(gam))
+    return {"s_opt": float(out[0]), "mse_opt": float(out[1]), "gamma": gam}
 

@@ -52,6 +52,10 @@
  *                                          0.98), asymmetric int4 error (Background:
  *                                          b = min, s = (max - min)/(2^k - 1); Setup: KV)
  *
+ *   kto_quant_sensitivity  optimal step of a symmetric k-bit uniform quantiser over a whole tensor and
+ *                                          the quantisation sensitivity Gamma of the Definition in the
+ *                                          Background ("Quantization Sensitivity"): the rise of the MSE
+ *                                          (Eq. 1) when the step moves off the optimum by a fraction of it
  *   kto_hadamard_rows   the online rotations R3-R5 ("Placement of the Rotations": random
  *                                          Hadamard matrices): y = (x * signs) H_d / sqrt(d) with
  *                                          the Sylvester matrix H_2m = [[H_m, H_m], [H_m, -H_m]]
@@ -651,6 +655,86 @@ void kto_fuse_rotation(const double *W, const double *R, int64_t k, int64_t d, i
         for (int64_t m = 0; m < d; ++m) acc += R[m * d + i] * W[m * k + j];
         Wout[i * k + j] = acc;
       }
+  }
+}
+
+/* MSE (Eq. 1) of the symmetric k-bit uniform quantiser with step s over y[0..count):
+ * q = clamp(rint(y / s), -L, L), L = 2^(bits-1) - 1; the decision y * (1/s) is taken in fp32 like
+ * every quantiser here, the error in fp64. */
+static double mse_at_step(const float *y, int64_t count, float s, int L) {
+  if (!(s > 0.0f)) {
+    double a = 0.0;
+    for (int64_t i = 0; i < count; ++i) a += (double)y[i] * (double)y[i];
+    return a / (double)count;
+  }
+  volatile float r = 1.0f / s;
+  double acc = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : acc)
+  for (int64_t i = 0; i < count; ++i) {
+    volatile float u = y[i] * r;
+    float q = rintf(u);
+    if (q > (float)L) q = (float)L;
+    if (q < -(float)L) q = -(float)L;
+    const double dd = (double)y[i] - (double)q * (double)s;
+    acc += dd * dd;
+  }
+  return acc / (double)count;
+}
+
+/*
+ * Optimal step by three rounds of a 32-point grid, then Gamma at the given fractions.
+ *   round 0: s_j = smax c_j, smax = amax / L, c_j = 2^(-j/4), j = 0..31 (down to smax / 215)
+ *   rounds 1, 2: 32 points spread evenly between the neighbours of the best point so far
+ *   (lo + (hi - lo) (j + 1) / 33 in fp32); the best of all points evaluated is s_opt.
+ *   gamma[i] = | MSE(s_opt (1 + alpha_i)) - MSE(s_opt) |.
+ * out[0] = s_opt, out[1] = MSE(s_opt).  Candidate steps are formed in fp32, one operation at a time.
+ */
+void kto_quant_sensitivity(const float *y, int64_t count, int bits, const float *alphas, int n_alpha,
+                           double *out, double *gamma) {
+  static const float c4[4] = {1.0f, 0.840896415f, 0.707106781f, 0.594603558f}; /* 2^(-k/4) */
+  const int L = (1 << (bits - 1)) - 1;
+  float amax = 0.0f;
+  for (int64_t i = 0; i < count; ++i) { const float a = fabsf(y[i]); if (a > amax) amax = a; }
+  const float smax = amax / (float)L;
+  float steps[32];
+  double mse[32];
+  float best_s = smax, lo = smax, hi = smax;
+  double best = -1.0;
+  for (int round = 0; round < 3; ++round) {
+    for (int j = 0; j < 32; ++j) {
+      if (round == 0) {
+        volatile float c = ldexpf(c4[j & 3], -(j >> 2));
+        steps[j] = smax * c;
+      } else {
+        volatile float span = hi - lo;
+        volatile float f = (float)(j + 1) / 33.0f;
+        volatile float inc = span * f;
+        steps[j] = lo + inc;
+      }
+      mse[j] = mse_at_step(y, count, steps[j], L);
+    }
+    int arg = 0;
+    for (int j = 1; j < 32; ++j) if (mse[j] < mse[arg]) arg = j;
+    float nlo, nhi;
+    if (round == 0) {            /* steps descend: neighbours j+1 (smaller) and j-1 (larger) */
+      nlo = steps[arg + 1 < 32 ? arg + 1 : arg];
+      nhi = steps[arg > 0 ? arg - 1 : arg];
+    } else {                     /* steps ascend inside (lo, hi) */
+      nlo = arg > 0 ? steps[arg - 1] : lo;
+      nhi = arg + 1 < 32 ? steps[arg + 1] : hi;
+    }
+    if (best < 0.0 || mse[arg] < best) { best = mse[arg]; best_s = steps[arg]; lo = nlo; hi = nhi; }
+    else { /* no better point in this round: shrink around the incumbent */
+      volatile float q1 = best_s - lo, q2 = hi - best_s;
+      lo = best_s - 0.25f * q1; hi = best_s + 0.25f * q2;
+    }
+  }
+  out[0] = (double)best_s;
+  out[1] = best;
+  for (int i = 0; i < n_alpha; ++i) {
+    volatile float f = 1.0f + alphas[i];
+    const float s = best_s * f;
+    gamma[i] = fabs(mse_at_step(y, count, s, L) - best);
   }
 }
 
