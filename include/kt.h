@@ -51,7 +51,8 @@ enum {
 
 typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
 typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3,
-               KT_OP_QUANT_METRICS = 4, KT_OP_FUSE_ROTATION = 5 } kt_op;
+               KT_OP_QUANT_METRICS = 4, KT_OP_FUSE_ROTATION = 5,
+               KT_OP_SENSITIVITY = 6 } kt_op;
 
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
@@ -226,6 +227,22 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
                                   float* Y, float* amax, float* threshold, float* err_sym,
                                   float* err_asym, int64_t* success,
                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Quantisation sensitivity of a tensor (Background: Definition "Quantization Sensitivity" and
+ * Eq. 1): for the symmetric `bits`-bit uniform quantiser q = clamp(rint(y / s), -L, L) s,
+ * L = 2^(bits-1) - 1, over ALL `count` entries of Y as one sample,
+ *   out[0] = s_opt, the step minimising MSE(s) (three rounds of a 32-point grid: s_max 2^(-j/4)
+ *            with s_max = max|y| / L, then twice 32 points between the neighbours of the best),
+ *   out[1] = MSE(s_opt),   gamma[i] = | MSE(s_opt (1 + alphas[i])) - MSE(s_opt) |.
+ *  Y       device fp32 [count] (e.g. the Y output of kt_rotate_quant_metrics).
+ *  alphas  device fp32 [n_alpha], n_alpha <= 31 (fractions of the optimal step, may be negative);
+ *  out [2], gamma [n_alpha]: device fp32.  The search runs on the device; no host sync.
+ * Workspace: kt_workspace_bytes(KT_OP_SENSITIVITY, 1, 1, 128, KT_F32).
+ */
+kt_status kt_quant_sensitivity(const float* Y, int64_t count, int32_t bits, const float* alphas,
+                               int32_t n_alpha, float* out, float* gamma,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The online rotations of "Placement of the Rotations" (R3, R4, R5: random Hadamard matrices

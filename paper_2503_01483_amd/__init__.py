@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     KT_OP_POOLED_LOSS_GRAD,
     KT_OP_QUANT_METRICS,
     KT_OP_FUSE_ROTATION,
+    KT_OP_SENSITIVITY,
     KtError,
     lib,
     lib_path,
@@ -28,6 +29,7 @@ from .binding import (  # noqa: F401
     kt_rotate_quant_metrics,
     kt_hadamard_rows,
     kt_fuse_rotation,
+    kt_quant_sensitivity,
     Workspace,
     kt_profile_enable,
     kt_profile_read,

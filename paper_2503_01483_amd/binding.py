@@ -10,10 +10,10 @@ _lib = None
 
 KT_F32, KT_BF16 = 0, 1
 KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD, KT_OP_QUANT_METRICS = 0, 1, 2, 3, 4
-KT_OP_FUSE_ROTATION = 5
+KT_OP_FUSE_ROTATION, KT_OP_SENSITIVITY = 5, 6
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
-           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_fuse_rotation", "kt_profile_enable", "kt_profile_read",
+           "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_fuse_rotation", "kt_quant_sensitivity", "kt_profile_enable", "kt_profile_read",
            "kt_profile_reset")
 
 
@@ -57,6 +57,8 @@ def lib():
     L.kt_hadamard_rows.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, vp]
     L.kt_fuse_rotation.restype = i32
     L.kt_fuse_rotation.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i32, vp, sz, vp]
+    L.kt_quant_sensitivity.restype = i32
+    L.kt_quant_sensitivity.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, sz, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
     L.kt_cayley_adam_step.restype = i32
@@ -244,6 +246,18 @@ def kt_fuse_rotation(W, R, side, *, out=None, workspace=None, stream=None):
     _check(lib().kt_fuse_rotation(_ptr(W), W.stride(0), _ptr(R), R.stride(0), _ptr(out), out.stride(0), k, d,
                                   int(side), _ptr(ws), ws.numel(), _stream(stream)))
     return out
+
+
+def kt_quant_sensitivity(Y, alphas, *, bits=4, workspace=None, stream=None):
+    """Returns (out [2] = {s_opt, MSE(s_opt)}, gamma [len(alphas)]) as device tensors."""
+    assert Y.dtype == torch.float32 and Y.is_contiguous() and alphas.dtype == torch.float32
+    out = torch.empty(2, dtype=torch.float32, device=Y.device)
+    gamma = torch.empty(alphas.numel(), dtype=torch.float32, device=Y.device)
+    need = kt_workspace_bytes(KT_OP_SENSITIVITY, 1, 1, 128, KT_F32)
+    ws = (workspace or Workspace(Y.device)).get(need)
+    _check(lib().kt_quant_sensitivity(_ptr(Y), Y.numel(), int(bits), _ptr(alphas), alphas.numel(), _ptr(out),
+                                      _ptr(gamma), _ptr(ws), ws.numel(), _stream(stream)))
+    return out, gamma
 
 
 def kt_profile_enable(max_records):

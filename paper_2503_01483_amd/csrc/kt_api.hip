@@ -64,6 +64,7 @@ constexpr int kNumCUs = 256;
 // feature row is contiguous, blocks follow each other feature-row-set by feature-row-set, so
 // the 256 rows a tile streams together span 2 MiB per block instead of one page per row.
 constexpr int64_t kTokenBlock = 4096;
+constexpr int kSensBlocks = 1024;  // workgroups of the sensitivity sweeps
 constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
 
@@ -677,6 +678,8 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
     case KT_OP_FUSE_ROTATION:  // n = the other dimension k of the weight
       if (n < 1) return 0;
       return round_up(d * d * 4, 256) + (size_t)n * d * 4;
+    case KT_OP_SENSITIVITY:
+      return (size_t)kSensBlocks * kSensSteps * 8 + 1024;
     case KT_OP_CAYLEY:
       return plan_cayley(batch, d).total;
     case KT_OP_FAKEQUANT:
@@ -934,6 +937,41 @@ kt_status kt_fuse_rotation(const float* W, int64_t ldw, const float* R, int64_t 
     e.M = (int)d; e.N = (int)k;
     if (!launch_gemm<TF>(RT, d, 0, (int)d, Wt, d, 0, (int)k, d, 0, 1, e, st))
       return fail(KT_ERR_DEVICE, "fusion GEMM launch failed");
+  }
+  return KT_OK;
+}
+
+kt_status kt_quant_sensitivity(const float* Y, int64_t count, int32_t bits, const float* alphas, int32_t n_alpha,
+                               float* out, float* gamma, void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  if (!Y || !out) return fail(KT_ERR_INVALID_ARG, "Y and out must not be null");
+  if (count < 1) return fail(KT_ERR_INVALID_ARG, "count must be positive");
+  if (bits < 2 || bits > 8) return fail(KT_ERR_INVALID_ARG, "bits must be in [2, 8]");
+  if (n_alpha < 0 || n_alpha > kSensSteps - 1) return fail(KT_ERR_INVALID_ARG, "at most 31 step fractions");
+  if (n_alpha > 0 && (!alphas || !gamma)) return fail(KT_ERR_INVALID_ARG, "alphas and gamma must not be null");
+  const size_t need = (size_t)kSensBlocks * kSensSteps * 8 + 1024;
+  kt_status s = check_ws(workspace, workspace_bytes, need);
+  if (s != KT_OK) return s;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  double* part = reinterpret_cast<double*>(ws);
+  double* dst = reinterpret_cast<double*>(ws + (size_t)kSensBlocks * kSensSteps * 8);
+  float* stt = reinterpret_cast<float*>(ws + (size_t)kSensBlocks * kSensSteps * 8 + 64);
+  const float L = (float)((1 << (bits - 1)) - 1);
+  const int nblocks = (int)(ceil_div(count, 256) < kSensBlocks ? ceil_div(count, 256) : kSensBlocks);
+  ProfScope prof(5, st);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<unsigned*>(stt), 64, 0u);
+  hipLaunchKernelGGL(sens_amax_kernel, dim3(nblocks), dim3(256), 0, st, Y, count,
+                     reinterpret_cast<unsigned*>(stt + 35));
+  hipLaunchKernelGGL(sens_select_kernel, dim3(1), dim3(256), 0, st, part, nblocks, 0, count, -1, L, stt, dst, alphas,
+                     (int)n_alpha, out, gamma);
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "sensitivity set-up launch failed");
+  for (int round = 0; round < 4; ++round) {
+    const int ns = round < 3 ? kSensSteps : 1 + n_alpha;
+    hipLaunchKernelGGL(sens_sweep_kernel, dim3(nblocks), dim3(256), 0, st, Y, count, stt, ns, L, part);
+    hipLaunchKernelGGL(sens_select_kernel, dim3(1), dim3(256), 0, st, part, nblocks, ns, count, round, L, stt, dst,
+                       alphas, (int)n_alpha, out, gamma);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "sensitivity sweep launch failed");
   }
   return KT_OK;
 }

@@ -765,4 +765,132 @@ __global__ __launch_bounds__(256) void transpose_f32_kernel(const float* __restr
   }
 }
 
+// ---- quantisation sensitivity (Background: Definition "Quantization Sensitivity", Eq. 1) ----
+// Device state of the search: st[0..31] candidate steps, st[32] = lo, st[33] = hi, st[34] = best step,
+// st[35] = amax; best MSE in dst[0] (fp64), sentinel -1 before the first round.
+// |y| maximum of a flat fp32 array; grid-stride; bit pattern max (order independent).
+__global__ __launch_bounds__(256) void sens_amax_kernel(const float* __restrict__ y, int64_t count,
+                                                        unsigned* __restrict__ amax_bits) {
+  __shared__ unsigned red[4];
+  unsigned m = 0u;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+    m = umax(m, abs_bits(y[i]));
+  m = wave_umax(m);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(amax_bits, umax(umax(red[0], red[1]), umax(red[2], red[3])));
+}
+
+// Sum of squared errors of NS candidate steps in one pass over y: part[block][NS] (fp64).
+// q = clamp(rint(y (1/s)), -L, L) in fp32, error in fp32 per element, fp64 across elements of a thread
+// every 64 elements and across the block.
+constexpr int kSensSteps = 32;
+__global__ __launch_bounds__(256) void sens_sweep_kernel(const float* __restrict__ y, int64_t count,
+                                                         const float* __restrict__ steps, int ns, float L,
+                                                         double* __restrict__ part) {
+  __shared__ double sh[4];
+  __shared__ float s_s[kSensSteps], s_r[kSensSteps];
+  if (threadIdx.x < kSensSteps) {
+    const float s = threadIdx.x < ns ? steps[threadIdx.x] : 0.f;
+    s_s[threadIdx.x] = s;
+    s_r[threadIdx.x] = s > 0.f ? __fdiv_rn(1.0f, s) : 0.f;
+  }
+  __syncthreads();
+  double acc[kSensSteps];
+#pragma unroll
+  for (int j = 0; j < kSensSteps; ++j) acc[j] = 0.0;
+  float facc[kSensSteps];
+#pragma unroll
+  for (int j = 0; j < kSensSteps; ++j) facc[j] = 0.f;
+  int pending = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+    const float v = y[i];
+#pragma unroll
+    for (int j = 0; j < kSensSteps; ++j) {
+      float q = rintf(__fmul_rn(v, s_r[j]));
+      q = fminf(fmaxf(q, -L), L);
+      const float dlt = v - q * s_s[j];
+      facc[j] = fmaf(dlt, dlt, facc[j]);
+    }
+    if (++pending == 64) {
+#pragma unroll
+      for (int j = 0; j < kSensSteps; ++j) { acc[j] += (double)facc[j]; facc[j] = 0.f; }
+      pending = 0;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kSensSteps; ++j) acc[j] += (double)facc[j];
+  for (int j = 0; j < ns; ++j) {
+    const double t = block_dsum_fast_256(acc[j], sh);
+    if (threadIdx.x == 0) part[(int64_t)blockIdx.x * kSensSteps + j] = t;
+  }
+}
+
+// One block: add the block partials in fixed order, pick the best candidate, write the next grid.
+// round 0..2 as in the search; round 3: the steps were {best, best (1 + alpha_i)}: write the outputs.
+__global__ __launch_bounds__(256) void sens_select_kernel(const double* __restrict__ part, int nblocks, int ns,
+                                                          int64_t count, int round, float L, float* __restrict__ st,
+                                                          double* __restrict__ dst, const float* __restrict__ alphas,
+                                                          int n_alpha, float* __restrict__ out,
+                                                          float* __restrict__ gamma) {
+  __shared__ double sh[4];
+  __shared__ double mse[kSensSteps];
+  if (round >= 0) {
+    for (int j = 0; j < ns; ++j) {
+      double v = 0.0;
+      for (int i = threadIdx.x; i < nblocks; i += 256) v += part[(int64_t)i * kSensSteps + j];
+      const double t = block_dsum_fast_256(v, sh);
+      if (threadIdx.x == 0) mse[j] = t / (double)count;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x != 0) return;
+  const float c4[4] = {1.0f, 0.840896415f, 0.707106781f, 0.594603558f};  // 2^(-k/4)
+  if (round < 0) {  // first grid: smax 2^(-j/4)
+    const float smax = __fdiv_rn(st[35], L);
+    for (int j = 0; j < 32; ++j) st[j] = __fmul_rn(smax, ldexpf(c4[j & 3], -(j >> 2)));
+    st[32] = st[33] = st[34] = smax;
+    dst[0] = -1.0;
+    return;
+  }
+  if (round == 3) {
+    out[0] = st[34];
+    out[1] = (float)dst[0];
+    for (int i = 0; i < n_alpha; ++i) gamma[i] = (float)fabs(mse[i + 1] - mse[0]);
+    return;
+  }
+  int arg = 0;
+  for (int j = 1; j < 32; ++j) if (mse[j] < mse[arg]) arg = j;
+  float lo = st[32], hi = st[33], best_s = st[34];
+  float nlo, nhi;
+  if (round == 0) {
+    nlo = st[arg + 1 < 32 ? arg + 1 : arg];
+    nhi = st[arg > 0 ? arg - 1 : arg];
+  } else {
+    nlo = arg > 0 ? st[arg - 1] : lo;
+    nhi = arg + 1 < 32 ? st[arg + 1] : hi;
+  }
+  if (dst[0] < 0.0 || mse[arg] < dst[0]) {
+    dst[0] = mse[arg]; best_s = st[arg]; lo = nlo; hi = nhi;
+  } else {
+    const float q1 = __fsub_rn(best_s, lo), q2 = __fsub_rn(hi, best_s);
+    float p1 = __fmul_rn(0.25f, q1), p2 = __fmul_rn(0.25f, q2);
+    asm volatile("" : "+v"(p1), "+v"(p2));  // keep the products rounded (no contraction)
+    lo = __fsub_rn(best_s, p1);
+    hi = __fadd_rn(best_s, p2);
+  }
+  st[32] = lo; st[33] = hi; st[34] = best_s;
+  if (round < 2) {
+    const float span = __fsub_rn(hi, lo);
+    for (int j = 0; j < 32; ++j) {
+      float inc = __fmul_rn(span, __fdiv_rn((float)(j + 1), 33.0f));
+      asm volatile("" : "+v"(inc));
+      st[j] = __fadd_rn(lo, inc);
+    }
+  } else {  // last: the best step and its perturbed copies
+    st[0] = best_s;
+    for (int i = 0; i < n_alpha; ++i) st[i + 1] = __fmul_rn(best_s, __fadd_rn(1.0f, alphas[i]));
+  }
+}
+
 }  // namespace kt
