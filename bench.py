@@ -40,7 +40,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the problem count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cayley", action="store_true", help="time loss+grad only")
-    ap.add_argument("--op", choices=["step", "fakequant", "quant-metrics", "hadamard"], default="step",
+    ap.add_argument("--op", choices=["step", "fakequant", "quant-metrics", "hadamard", "sensitivity"], default="step",
                     help="what a 'step' is: the training step (default, the headline metric) or one call of "
                          "kt_rotate_quant_metrics (evaluation-side figures) on the same activations")
     ap.add_argument("--loss", choices=["row", "pooled"], default="row",
@@ -119,6 +119,16 @@ def main():
             kt.kt_rotate_fakequant_int4(X, Rw, clip_ratio=1.0, scales_out=fq_scales, codes=fq_codes, err=fq_err,
                                         workspace=ws)
 
+    if args.op == "sensitivity":
+        ws.get(kt.kt_workspace_bytes(kt.KT_OP_QUANT_METRICS, 1, n, d, kt.KT_BF16 if bf16 else kt.KT_F32))
+        Ys = torch.empty((1, n, d), device=dev)
+        kt.kt_rotate_quant_metrics(X[0:1], Rw[0:1], quantile=1.0, Y=Ys, workspace=ws)
+        s_alphas = torch.tensor([0.05, 0.1, 0.2], device=dev)
+        s_out = [None, None]
+
+        def step():  # noqa: F811
+            s_out[0], s_out[1] = kt.kt_quant_sensitivity(Ys, s_alphas, bits=4, workspace=ws)
+
     if args.op == "hadamard":
         Xh = X.reshape(batch * n, d)
         Yh = torch.empty_like(Xh)
@@ -140,6 +150,23 @@ def main():
     elapsed = time.perf_counter() - t0
     prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
+    if args.op == "sensitivity":
+        ms = 1e3 * elapsed / args.steps
+        evals = float(n) * d * 4 * 32          # 4 sweeps x 32 candidate slots per element
+        lane_ops = evals * 7                     # mul, rint, min, max, fma, fma + the fp64 flush share
+        peak = 256 * 4 * 16 * 2.4e9 / 1e12       # fp32 vector lanes x clock, one operation per lane and cycle
+        print(json.dumps({
+            "metric": "elements/sec through kt_quant_sensitivity (optimal int4 step + sensitivity of one tensor)",
+            "value": round(float(n) * d * args.steps / elapsed, 1), "unit": "elements/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"{args.config}: Y = X R of problem 0, {n * d} fp32 entries, 3 fractions"},
+            "roofline": {"bound": "alu", "kernel": "sens_sweep_kernel (4 launches per call)",
+                         "achieved": round(lane_ops / (ms * 1e-3) / 1e12, 2), "peak": round(peak, 1), "unit": "Tlane-op/s",
+                         "frac": round(lane_ops / (ms * 1e-3) / 1e12 / peak, 4), "traffic": None},
+            "s_opt": float(s_out[0][0]), "mse_opt": float(s_out[0][1]), "gamma": s_out[1].cpu().tolist(),
+            "cpu_baseline": None}))
+        return
     if args.op == "fakequant":
         ms = 1e3 * elapsed / args.steps
         flops_call = 4.0 * batch * n * d * d      # two GEMM passes: row maxima, then quantise the recomputed y
