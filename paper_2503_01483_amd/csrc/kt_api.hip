@@ -824,6 +824,18 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   ProfScope prof(5, st);
+  if (!p.fp32 && d == 128) {  // one pass over X (kt_fused_d128.h)
+    bf16* RT = reinterpret_cast<bf16*>(ws + p.o_rt);
+    if (!prep_rt<bf16>(R, ldr, r_dtype, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
+    const int64_t tiles = ceil_div(n, 32);
+    int64_t wgs = ceil_div(4 * kNumCUs, batch);  // about four workgroups per CU over all problems
+    if (wgs > ceil_div(tiles, 4)) wgs = ceil_div(tiles, 4);
+    hipLaunchKernelGGL(quant_d128_kernel, dim3((unsigned)wgs, (unsigned)batch), dim3(256), 0, st,
+                       static_cast<const bf16*>(X), ldx, n * ldx, RT, (int)n, clip_ratio, scales_in, scales_out, codes,
+                       reinterpret_cast<float2*>(err));
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "d=128 fake-quant launch failed");
+    return KT_OK;
+  }
   if (p.fp32)
     return run_quant<float, TF, TF>(p, X, ldx, R, ldr, r_dtype, batch, n, d, clip_ratio, scales_in,
                                     scales_out, codes, err, ws, st);

@@ -386,4 +386,123 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
   if (tid == 0) loss_part[(int64_t)b * S + wg] = total;
 }
 
+// ---- single-pass rotate + int4 fake-quant for d = 128 (bf16) -------------------------------
+// A lane pair holds a whole rotated token row, so the row maximum, the scale, the codes and the
+// error sums all come out of ONE pass over X (the generic path rotates twice: maxima, then codes).
+// Every wave is on its own: 32-token tiles, its rows staged through 8 KiB of private LDS (loads of
+// the next tile in flight), R^T fragments in accumulation registers, no workgroup barrier.
+// Arithmetic identical to the generic path: s = (clip amax) / 7, q = clamp(rint(y (1/s)), -7, 7).
+// grid = (waves / 4, batch).
+__global__ __launch_bounds__(256) void quant_d128_kernel(const __bf16* __restrict__ X, int64_t ldx,
+                                                         int64_t x_batch_stride, const __bf16* __restrict__ RT,
+                                                         int n, float clip, const float* __restrict__ scales_in,
+                                                         float* __restrict__ scales_out, int8_t* __restrict__ codes,
+                                                         float2* __restrict__ err) {
+  __shared__ __align__(16) char lds_all[4 * 32 * 256];
+  constexpr int D = 128;
+  const int b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  char* lds = lds_all + wave * (32 * 256);
+  X += (int64_t)b * x_batch_stride;
+  RT += (int64_t)b * D * D;
+  const int tiles = (n + 31) / 32;
+  const int wave_id = blockIdx.x * 4 + wave, stride = gridDim.x * 4;
+
+  intx4 rtf[8][4];
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      rtf[s][mb] = *reinterpret_cast<const intx4*>(RT + (mb * 32 + l32) * D + (2 * s + half) * 8);
+      asm volatile("" : "+a"(rtf[s][mb]));
+    }
+
+  // chunk i of a lane: tile row (lane >> 4) + 4 i, 16-byte column lane & 15
+  intx4 nxt[8];
+  auto request = [&](int tile) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = tile * 32 + (lane >> 4) + 4 * i;
+      intx4 v = {0, 0, 0, 0};
+      if (tile < tiles && row < n) v = *reinterpret_cast<const intx4*>(X + (int64_t)row * ldx + (lane & 15) * 8);
+      nxt[i] = v;
+    }
+  };
+  request(wave_id);
+  for (int tile = wave_id; tile < tiles; tile += stride) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the previous tile's fragment reads are done
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = (lane >> 4) + 4 * i;
+      *reinterpret_cast<intx4*>(lds + row * 256 + (((lane & 15) ^ f128_xkey(row)) << 4)) = nxt[i];
+    }
+    request(tile + stride);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // LDS of one wave executes in order; keep the compiler in order too
+    floatx16 acc[4];
+    {
+      const char* xrow = lds + l32 * 256;
+      intx4 xb[2];
+      xb[0] = *reinterpret_cast<const intx4*>(xrow + (((0 + half) ^ f128_xkey(l32)) << 4));
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        if (s + 1 < 8)
+          xb[(s + 1) & 1] = *reinterpret_cast<const intx4*>(xrow + (((2 * (s + 1) + half) ^ f128_xkey(l32)) << 4));
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          if (s == 0)
+            mfma_y_first(acc[mb], rtf[0][mb], xb[0]);
+          else
+            mfma_y(acc[mb], rtf[s][mb], xb[s & 1]);
+        }
+      }
+      mfma_result_fence(acc[0], acc[1], acc[2], acc[3]);
+    }
+    const int token = tile * 32 + l32;
+    const bool tv = token < n;
+    const int64_t to = (int64_t)b * n + token;
+    float s;
+    if (scales_in) {
+      s = tv ? scales_in[to] : 0.f;
+    } else {
+      float a = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a = fmaxf(a, fabsf(acc[mb][r]));
+      a = fmaxf(a, __shfl_xor(a, 32));
+      s = __fdiv_rn(__fmul_rn(clip, a), 7.0f);
+    }
+    if (scales_out && tv && half == 0) scales_out[to] = s;
+    if (codes || err) {
+      const bool live = s > 0.f;
+      const float rinv = live ? __fdiv_rn(1.0f, s) : 0.f;
+      float e2 = 0.f, y2 = 0.f;
+      int8_t* crow = codes + to * D;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          unsigned pack = 0u;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float y = acc[mb][4 * g + e];
+            float q = rintf(__fmul_rn(y, rinv));
+            q = fminf(fmaxf(q, -7.f), 7.f);
+            if (!live) q = 0.f;
+            const float diff = y - q * s;
+            e2 = fmaf(diff, diff, e2);
+            y2 = fmaf(y, y, y2);
+            pack |= ((unsigned)(int)q & 0xffu) << (8 * e);
+          }
+          if (codes && tv) *reinterpret_cast<unsigned*>(crow + mb * 32 + 8 * g + 4 * half) = pack;
+        }
+      if (err) {
+        e2 += __shfl_xor(e2, 32);
+        y2 += __shfl_xor(y2, 32);
+        if (half == 0 && tv) err[to] = make_float2(e2, y2);
+      }
+    }
+  }
+}
+
 }  // namespace kt

@@ -63,7 +63,7 @@ def test_bit_exact_hadamard_of_small_integers(dtype):
         assert np.allclose(e[0], o["err"], rtol=1e-4, atol=1e-30)
 
 
-@pytest.mark.parametrize("dtype,n,d,batch", [("bf16", 600, 256, 1), ("bf16", 200, 128, 2), ("bf16", 300, 512, 1),
+@pytest.mark.parametrize("dtype,n,d,batch", [("bf16", 600, 256, 1), ("bf16", 200, 128, 2), ("bf16", 5000, 128, 3), ("bf16", 300, 512, 1),
                                               ("f32", 500, 256, 1)])
 def test_general_rotation_with_given_scales(dtype, n, d, batch):
     for b in range(batch):
