@@ -89,3 +89,50 @@ def test_argument_errors_are_synchronous():
 def test_binding_has_no_fallback():
     src = open(os.path.join(ROOT, "paper_2503_01483_amd", "binding.py")).read()
     assert "oracle" not in src
+
+
+def test_argument_errors_of_the_widened_entry_points():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every call below must fail before any launch
+    ws = ctypes.c_void_p(0x100000)
+    big = 1 << 40
+    st = L.kt_rotate_quant_metrics(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.5, None, None, None, None, None, None,
+                                   ws, big, None)
+    assert st == 1 and "quantile" in kt.kt_last_error()
+    st = L.kt_rotate_quant_metrics(fake, 16384, fake, 16384, 1, 16, 16384, 1, 1, 0.98, None, None, None, None, None,
+                                   None, ws, big, None)
+    assert st == 6 and "8192" in kt.kt_last_error()
+    st = L.kt_hadamard_rows(fake, 96, fake, 96, None, 4, 96, 0, None)
+    assert st == 2 and "power of two" in kt.kt_last_error()
+    st = L.kt_hadamard_rows(fake, 130, fake, 128, None, 4, 128, 0, None)
+    assert st == 2 and "aligned" in kt.kt_last_error()
+    st = L.kt_fuse_rotation(fake, 128, fake, 128, fake, 128, 64, 128, 2, ws, big, None)
+    assert st == 1 and "side" in kt.kt_last_error()
+    st = L.kt_fuse_rotation(fake, 128, fake, 128, fake, 128, 64, 100, 0, ws, big, None)
+    assert st == 2
+    st = L.kt_quant_sensitivity(fake, 100, 1, None, 0, fake, None, ws, big, None)
+    assert st == 1 and "bits" in kt.kt_last_error()
+    st = L.kt_quant_sensitivity(fake, 100, 4, None, 3, fake, None, ws, big, None)
+    assert st == 1 and "alphas" in kt.kt_last_error()
+    st = L.kt_pooled_kurtosis_loss_grad(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.8, -1.0, fake, None, None, ws, big,
+                                        None)
+    assert st == 1 and "rms_eps" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, 128, fake, 128, 1, 16, 128, 1, 1, 0.0, fake, None, None, ws, 16, None)
+    assert st == 4                   # workspace too small
+
+
+def test_workspace_queries_of_the_widened_ops():
+    f = kt.kt_workspace_bytes
+    assert f(kt.KT_OP_POOLED_LOSS_GRAD, 256, 4096, 128, kt.KT_BF16) > f(kt.KT_OP_LOSS_GRAD, 256, 4096, 128, kt.KT_BF16)
+    assert f(kt.KT_OP_QUANT_METRICS, 1, 1024, 256, kt.KT_BF16) >= 1024 * 256 * 4
+    assert f(kt.KT_OP_FUSE_ROTATION, 1, 1000, 256, kt.KT_F32) >= 1000 * 256 * 4
+    assert f(kt.KT_OP_SENSITIVITY, 1, 1, 128, kt.KT_F32) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
