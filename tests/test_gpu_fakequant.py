@@ -99,3 +99,22 @@ def test_scales_only_and_zero_rows():
     kt.kt_rotate_fakequant_int4(X.cuda(), R.cuda(), scales_out=so)
     torch.cuda.synchronize()
     assert np.array_equal(so.cpu().numpy(), s)
+
+
+def test_single_pass_d128_batched_with_row_stride_matches_the_contiguous_call():
+    n, d, batch = 700, 128, 3
+    Xfull = ktgen.make_x(n * batch, 192, seed=17, outlier_cols=3, outlier_scale=30.0, dtype="bf16").reshape(batch, n, 192).cuda()
+    Xv, Xc = Xfull[:, :, :d], Xfull[:, :, :d].contiguous()
+    R = torch.stack([ktgen.random_orthogonal(d, seed=50 + b) for b in range(batch)]).cuda()
+    outs = []
+    for X in (Xv, Xc):
+        codes = torch.empty((batch, n, d), dtype=torch.int8, device="cuda")
+        scales = torch.empty((batch, n), device="cuda")
+        err = torch.empty((batch, n, 2), device="cuda")
+        kt.kt_rotate_fakequant_int4(X, R, scales_out=scales, codes=codes, err=err)
+        torch.cuda.synchronize()
+        outs.append((codes.cpu(), scales.cpu(), err.cpu()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    ref = oracle.fakequant_int4(ktgen.to_f64(Xc[1].cpu()), ktgen.to_f64(ktgen.bf16_round(R[1].cpu())))
+    assert np.allclose(outs[0][1][1].numpy(), ref["scales"], rtol=1e-2)

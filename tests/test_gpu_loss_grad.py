@@ -171,3 +171,13 @@ def test_fused_d128_degenerate_rows_and_determinism():
     X2, R2, _ = ktgen.make_problem("C4", seed=5, n=10000, batch=3)
     a, b = gpu_loss_grad(X2, R2), gpu_loss_grad(X2, R2)
     assert np.array_equal(a["dR"], b["dR"]) and np.array_equal(a["loss"], b["loss"])
+
+
+def test_fused_d128_batched_with_row_stride():
+    # a [batch][n][192] buffer viewed as 128 columns: row stride 192, batch stride n * 192
+    n, d, batch = 1000, 128, 3
+    Xfull = ktgen.make_x(n * batch, 192, seed=13, outlier_cols=4, outlier_scale=40.0, dtype="bf16").reshape(batch, n, 192).cuda()
+    X = Xfull[:, :, :d]
+    R = torch.stack([ktgen.random_orthogonal(d, seed=30 + b) for b in range(batch)])
+    o = oracle_loss_grad(X.cpu().contiguous(), R)
+    check_loss_grad(gpu_loss_grad(X, R), o, TOL_BF16)
