@@ -8,7 +8,10 @@
  * back-propagate to dL/dR = X^T (dL/dY), and retract R onto the orthogonal group
  * with a Cayley step; plus the per-token symmetric int4 fake quantiser used to
  * check the rotated activations (Background, "Uniform Quantization for k-bit
- * Precision"; Setup).
+ * Precision"; Setup).  Further entry points cover the optimiser and the loss exactly as
+ * the paper names them (Cayley Adam, pooled kurtosis after an RMSNorm), the quantities the
+ * paper evaluates rotations with, and the application of rotations (Hadamard rows, fusion
+ * into weights).
  *
  * Conventions common to every entry point
  *  - All data pointers are DEVICE pointers on the current HIP device unless the
@@ -20,7 +23,8 @@
  *  - Argument errors are reported synchronously (nothing is enqueued, nothing is
  *    written) through the return value; kt_last_error() gives the text.
  *    Faults on the device surface at the caller's next synchronisation.
- *  - Inputs and outputs must not overlap, except R in kt_cayley_step.
+ *  - Inputs and outputs must not overlap, except the in/out arguments (R, M, v of the
+ *    Cayley steps) and Y == X in kt_hadamard_rows.
  *  - `batch` independent problems are laid out back to back: problem b of X
  *    starts at X + b*n*ldx elements, of R at R + b*d*ldr, of dR at dR + b*d*d.
  *  - Results are deterministic: the same inputs give bitwise the same outputs
