@@ -98,3 +98,43 @@ def test_c4_full_size_sampled_problems():
     # every problem: loss is the mean of its row values
     means = rk.double().mean(1)
     assert float(((loss.double() - means).abs() / means).max()) <= 1e-5
+
+
+@pytest.mark.parametrize("name,rows_checked,chunk", [("C2", 128, 2048), ("C5", 48, 256)])
+def test_c2_c5_full_size(name, rows_checked, chunk):
+    """C2 (d = 2048, n = 65536) and C5 (d = 8192, n = 1048576: 16 GiB of X, 4096-token blocks of the
+    token-minor copies, split-K) in the launch configuration bench.py times: sampled rows and a row
+    chunk against the oracle, the gradient invariants, and additivity over two halves."""
+    X, R, cfg = ktgen.make_problem(name, seed=0, device="cuda")
+    b, n, d = X.shape
+    ws = kt.Workspace()
+    rk = torch.empty((1, n), device="cuda")
+    dR = torch.empty((1, d, d), device="cuda")
+    loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    rk_h = rk[0].cpu().numpy().astype(np.float64)
+    Rb = ktgen.to_f64(ktgen.bf16_round(R[0]))
+    assert abs(loss.item() - rk_h.mean()) <= 1e-5 * rk_h.mean()
+    rows = np.random.default_rng(1).choice(n, size=rows_checked, replace=False)
+    o = oracle.loss_grad(ktgen.to_f64(X[0, torch.as_tensor(rows, device="cuda")]), Rb, want_dR=False)
+    assert np.max(np.abs(rk_h[rows] - o["row_kurt"]) / o["row_kurt"]) <= 2e-2
+    dR_d = dR[0].double()
+    nrm = float(dR_d.norm())
+    assert float(dR_d.sum(1).norm()) <= 1e-3 * nrm * np.sqrt(d)
+    assert abs(float((dR_d * torch.as_tensor(Rb, device="cuda")).sum())) <= 1e-3 * nrm * np.linalg.norm(Rb)
+    # a chunk the oracle can do at the real d
+    l2 = torch.empty(1, device="cuda")
+    d2 = torch.empty((1, d, d), device="cuda")
+    kt.kt_kurtosis_loss_grad(X[:, :chunk], R, loss=l2, dR=d2, workspace=ws)
+    torch.cuda.synchronize()
+    oc = oracle.loss_grad(ktgen.to_f64(X[0, :chunk]), Rb)
+    assert abs(l2.item() - oc["loss"]) <= 2e-2 * oc["loss"]
+    assert rel_fro(d2[0].cpu().numpy(), oc["dR"]) <= 2e-2
+    # additivity over two halves ties the full gradient to the halves
+    acc = torch.zeros((d, d), dtype=torch.float64, device="cuda")
+    h = n // 2
+    for c in range(2):
+        kt.kt_kurtosis_loss_grad(X[:, c * h:(c + 1) * h], R, loss=l2, dR=d2, workspace=ws)
+        acc += h * d2[0].double()
+    torch.cuda.synchronize()
+    assert float((n * dR_d - acc).norm()) <= 5e-3 * float(acc.norm())
