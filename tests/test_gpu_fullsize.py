@@ -138,3 +138,26 @@ def test_c2_c5_full_size(name, rows_checked, chunk):
         acc += h * d2[0].double()
     torch.cuda.synchronize()
     assert float((n * dR_d - acc).norm()) <= 5e-3 * float(acc.norm())
+
+
+def test_c5_size_cayley_step_against_a_double_precision_solve():
+    """d = 8192 (the C5 rotation): too large for the CPU oracle's plain LU in test time, so the step is
+    compared with the same formula evaluated by the framework's fp64 solver on the device
+    (R+ = (I + lr/2 A)^-1 (I - lr/2 A) R, A = G R^T - R G^T), an independent library routine."""
+    d, lr = 8192, 1e-2
+    R = ktgen.random_orthogonal(d, seed=2, device="cuda").unsqueeze(0).contiguous()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    G = torch.randn((1, d, d), generator=g, device="cuda") / np.sqrt(d)
+    Rn = R.clone()
+    oe = torch.zeros(1, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kt.kt_cayley_step(Rn, G, lr, ortho_err=oe, info=info)
+    torch.cuda.synchronize()
+    Rd, Gd = R[0].double(), G[0].double()
+    A = Gd @ Rd.T - Rd @ Gd.T
+    I = torch.eye(d, dtype=torch.float64, device="cuda")
+    ref = torch.linalg.solve(I + 0.5 * lr * A, (I - 0.5 * lr * A) @ Rd)
+    step = ref - Rd
+    assert float((Rn[0].double() - Rd - step).norm() / step.norm()) <= 1e-4
+    assert 1 <= info.item() <= 32 and oe.item() < 1e-6
+    assert float((Rn[0].double().T @ Rn[0].double() - I).abs().max()) < 1e-6
