@@ -143,11 +143,15 @@ def main():
     kt.kt_profile_enable(8 * args.steps + 8)
     kt.kt_profile_reset()
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()
         step()
+    marks[args.steps].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
     if args.op == "sensitivity":
@@ -295,7 +299,9 @@ def main():
     out = {
         "metric": "calibration tokens/sec through kurtosis loss+grad step; % of bf16 MFMA peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4), "ms_per_step_min": round(per_step[0], 4),
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: n={n} tokens x d={d}, batch={batch}, "
                                f"{'pooled ' if pooled else ''}loss+grad{'' if args.no_cayley else ('+Cayley Adam' if adam else '+Cayley')} step, lr={lr}",
