@@ -54,7 +54,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (token rows would shard over "
-              "GPUs with one all-reduce of dR per step, see DESIGN.md)", file=sys.stderr)
+              "GPUs with one all-reduce of dR per step)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -236,7 +236,7 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
  * Quantisation sensitivity of a tensor (Background: Definition "Quantization Sensitivity" and
  * Eq. 1): for the symmetric `bits`-bit uniform quantiser q = clamp(rint(y / s), -L, L) s,
  * L = 2^(bits-1) - 1, over ALL `count` entries of Y as one sample,
- *   out[0] = s_opt, the step minimising MSE(s) (three rounds of a 32-point grid: s_max 2^(-j/4)
+ *   out[0] = s_opt, the step minimising MSE(s) (three stages of a 32-point grid: s_max 2^(-j/4)
  *            with s_max = max|y| / L, then twice 32 points between the neighbours of the best),
  *   out[1] = MSE(s_opt),   gamma[i] = | MSE(s_opt (1 + alphas[i])) - MSE(s_opt) |.
  *  Y       device fp32 [count] (e.g. the Y output of kt_rotate_quant_metrics).

@@ -682,9 +682,9 @@ static double mse_at_step(const float *y, int64_t count, float s, int L) {
 }
 
 /*
- * Optimal step by three rounds of a 32-point grid, then Gamma at the given fractions.
- *   round 0: s_j = smax c_j, smax = amax / L, c_j = 2^(-j/4), j = 0..31 (down to smax / 215)
- *   rounds 1, 2: 32 points spread evenly between the neighbours of the best point so far
+ * Optimal step by three stages of a 32-point grid, then Gamma at the given fractions.
+ *   stage 0: s_j = smax c_j, smax = amax / L, c_j = 2^(-j/4), j = 0..31 (down to smax / 215)
+ *   stages 1, 2: 32 points spread evenly between the neighbours of the best point so far
  *   (lo + (hi - lo) (j + 1) / 33 in fp32); the best of all points evaluated is s_opt.
  *   gamma[i] = | MSE(s_opt (1 + alpha_i)) - MSE(s_opt) |.
  * out[0] = s_opt, out[1] = MSE(s_opt).  Candidate steps are formed in fp32, one operation at a time.

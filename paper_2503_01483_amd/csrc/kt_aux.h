@@ -827,7 +827,7 @@ __global__ __launch_bounds__(256) void sens_sweep_kernel(const float* __restrict
 }
 
 // One block: add the block partials in fixed order, pick the best candidate, write the next grid.
-// round 0..2 as in the search; round 3: the steps were {best, best (1 + alpha_i)}: write the outputs.
+// stage 0..2 as in the search; stage 3: the steps were {best, best (1 + alpha_i)}: write the outputs.
 __global__ __launch_bounds__(256) void sens_select_kernel(const double* __restrict__ part, int nblocks, int ns,
                                                           int64_t count, int round, float L, float* __restrict__ st,
                                                           double* __restrict__ dst, const float* __restrict__ alphas,
