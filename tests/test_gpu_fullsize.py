@@ -161,3 +161,43 @@ def test_c5_size_cayley_step_against_a_double_precision_solve():
     assert float((Rn[0].double() - Rd - step).norm() / step.norm()) <= 1e-4
     assert 1 <= info.item() <= 32 and oe.item() < 1e-6
     assert float((Rn[0].double().T @ Rn[0].double() - I).abs().max()) < 1e-6
+
+
+def test_c3_full_size_pooled_loss():
+    """The paper-literal pooled loss at C3 size.  The CPU oracle cannot rotate 131072 x 4096 in test
+    time; the pooled kurtosis of the definition is evaluated in fp64 by the framework's matmul on the
+    device instead (an independent library routine on the same bf16 values), the gradient by the
+    invariants the RMSNorm forces (every row of dL/dY is orthogonal to y, so <dR, R> = 0) and by
+    a row chunk against the oracle."""
+    X, R, cfg = ktgen.make_problem("C3", seed=0, device="cuda")
+    b, n, d = X.shape
+    ws = kt.Workspace()
+    kap = torch.zeros(1, device="cuda")
+    dR = torch.empty((1, d, d), device="cuda")
+    loss = kt.kt_pooled_kurtosis_loss_grad(X, R, kappa=kap, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    Rb = R[0].to(torch.bfloat16).double()
+    s1 = torch.zeros((), dtype=torch.float64, device="cuda")
+    parts = []
+    for c in range(0, n, 16384):                      # fp64 definition, chunked to bound memory
+        Y = X[0, c:c + 16384].double() @ Rb
+        Z = Y / (Y * Y).mean(1, keepdim=True).sqrt()
+        parts.append(torch.stack([Z.sum(), (Z ** 2).sum(), (Z ** 3).sum(), (Z ** 4).sum()]))
+    T = torch.stack(parts).sum(0) / (n * d)
+    mu, r2, r3, r4 = [float(v) for v in T]
+    m2 = r2 - mu * mu
+    m4 = r4 - 4 * mu * r3 + 6 * mu * mu * r2 - 3 * mu ** 4
+    kappa_ref = m4 / (m2 * m2)
+    assert abs(kap.item() - kappa_ref) <= 2e-2 * kappa_ref
+    assert abs(loss.item() - abs(kappa_ref - 1.8)) <= 2e-2 * kappa_ref
+    dR_d = dR[0].double()
+    assert abs(float((dR_d * Rb).sum())) <= 1e-3 * float(dR_d.norm()) * float(Rb.norm())
+    # a chunk the oracle can do, at the real d
+    m = 512
+    l2 = torch.empty(1, device="cuda")
+    d2 = torch.empty((1, d, d), device="cuda")
+    kt.kt_pooled_kurtosis_loss_grad(X[:, :m], R, loss=l2, dR=d2, workspace=ws)
+    torch.cuda.synchronize()
+    oc = oracle.pooled_loss_grad(ktgen.to_f64(X[0, :m]), ktgen.to_f64(ktgen.bf16_round(R[0])))
+    assert abs(l2.item() - oc["loss"]) <= 2e-2 * oc["kappa"]
+    assert rel_fro(d2[0].cpu().numpy(), oc["dR"]) <= 2e-2
