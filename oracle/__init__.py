@@ -20,5 +20,7 @@ from .binding import (  # noqa: F401
     quant_metrics,
     quant_sensitivity,
     hadamard_rows,
+    hadamard_factor,
+    hadamard_matrix,
     fuse_rotation,
 )

@@ -52,7 +52,11 @@ def _load():
     lib.kto_quant_metrics.argtypes = [dp, dp, fp, i64, i64, ctypes.c_double, fp, fp, dp, dp]
     lib.kto_quant_metrics.restype = ctypes.c_int64
     lib.kto_hadamard_rows.argtypes = [dp, dp, i64, i64, dp]
-    lib.kto_hadamard_rows.restype = None
+    lib.kto_hadamard_rows.restype = ctypes.c_int
+    lib.kto_hadamard_factor.argtypes = [i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int)]
+    lib.kto_hadamard_factor.restype = ctypes.c_int
+    lib.kto_hadamard_matrix.argtypes = [i64, ctypes.c_int, ctypes.POINTER(ctypes.c_int8)]
+    lib.kto_hadamard_matrix.restype = None
     lib.kto_fuse_rotation.argtypes = [dp, dp, i64, i64, ctypes.c_int, dp]
     lib.kto_fuse_rotation.restype = None
     lib.kto_quant_sensitivity.argtypes = [fp, i64, ctypes.c_int, fp, ctypes.c_int, dp, dp]
@@ -195,14 +199,30 @@ def quant_metrics(X, R, quantile=0.98, Y=None):
     return {"success": int(succ), "amax": amax, "thr": thr, "err_sym": es, "err_asym": ea}
 
 
+def hadamard_factor(d):
+    """d = m * 2^k as the library splits it: (m, 2^k, kind), kind 0 Sylvester / 1 Paley I / 2 Paley II;
+    None when d has no construction."""
+    m, p2, kind = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int()
+    if _load().kto_hadamard_factor(int(d), ctypes.byref(m), ctypes.byref(p2), ctypes.byref(kind)) != 0:
+        return None
+    return int(m.value), int(p2.value), int(kind.value)
+
+
+def hadamard_matrix(m, kind):
+    """The order-m factor H_m (entries +-1) of the given kind."""
+    H = np.empty((m, m), dtype=np.int8)
+    _load().kto_hadamard_matrix(int(m), int(kind), H.ctypes.data_as(ctypes.POINTER(ctypes.c_int8)))
+    return H
+
+
 def hadamard_rows(X, signs=None):
-    """Y = (X * signs) H_d / sqrt(d), rows of X; d a power of two."""
+    """Y = (X * signs) H_d / sqrt(d), rows of X; H_d = H_m (x) Sylvester_{2^k}."""
     X = _d(X)
     n, d = X.shape
-    assert d & (d - 1) == 0
     sg = None if signs is None else _d(signs)
     Y = np.empty((n, d), dtype=np.float64)
-    _load().kto_hadamard_rows(_p(X), _p(sg), n, d, _p(Y))
+    if _load().kto_hadamard_rows(_p(X), _p(sg), n, d, _p(Y)) != 0:
+        raise ValueError(f"no Hadamard construction for d = {d}")
     return Y
 
 

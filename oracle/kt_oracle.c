@@ -57,8 +57,9 @@
  *                                          Background ("Quantization Sensitivity"): the rise of the MSE
  *                                          (Eq. 1) when the step moves off the optimum by a fraction of it
  *   kto_hadamard_rows   the online rotations R3-R5 ("Placement of the Rotations": random
- *                                          Hadamard matrices): y = (x * signs) H_d / sqrt(d) with
- *                                          the Sylvester matrix H_2m = [[H_m, H_m], [H_m, -H_m]]
+ *                                          Hadamard matrices): y = (x * signs) H_d / sqrt(d), H_d the
+ *                                          Sylvester matrix for powers of two, else a Paley matrix
+ *                                          of small order (x) a Sylvester matrix
  *   kto_fuse_rotation   merging a fusible rotation into a weight matrix ("Placement of
  *                                          the Rotations"): W R or R^T W
  *
@@ -614,24 +615,125 @@ int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, i
 }
 
 /*
- * Y[i][:] = (X[i][:] * signs) H_d / sqrt(d), d a power of two, H_d the Sylvester-Hadamard matrix
- * written out entry by entry: H[a][b] = (-1)^popcount(a & b)  (the closed form of the recursion
- * H_1 = [1], H_2m = [[H_m, H_m], [H_m, -H_m]]).  signs (d values +-1) may be NULL.
- * Plain O(d^2) per row: this is the definition, not a fast transform.
+ * Hadamard matrices for the online rotations ("Placement of the Rotations": random Hadamard
+ * matrices; the hidden and FFN sizes of the models in the Setup are m 2^k with small m, not
+ * always powers of two).  The paper does not say which Hadamard matrix of a given order is meant:
+ * any one is an orthogonal rotation after scaling.  This library fixes
+ *   H_d = H_m (x) S_{2^k}     (Kronecker product, index a 2^k + b, a < m, b < 2^k)
+ * with S the Sylvester matrix and H_m, for d = r 2^t with r odd:
+ *   r = 1:  m = 1 when t <= 12, else m = max(4, 2^(t-12)); H_m = S_m (so H_d = S_d always)
+ *   r > 1:  m = r 2^j for the smallest j >= 2 (m <= 256) that admits
+ *           Paley's first construction  (q = m - 1 prime; then q = 3 mod 4), else
+ *           Paley's second construction (q = m/2 - 1 prime with q = 1 mod 4).
+ * Paley I:  H = I + S,  S = [[0, 1^T], [-1, Q]],  Q[u][v] = chi(u - v) the quadratic character
+ *           of Z_q (Q is skew for q = 3 mod 4).
+ * Paley II: C = [[0, 1^T], [1, Q]] (symmetric for q = 1 mod 4),  H = [[C + I, C - I], [C - I, -C - I]].
+ * Everything below is the definition written out: O(q) per character value, O(d^2) per row.
  */
-void kto_hadamard_rows(const double *X, const double *signs, int64_t n, int64_t d, double *Y) {
+static int kto_is_prime(int64_t q) {
+  if (q < 2) return 0;
+  for (int64_t t = 2; t * t <= q; ++t)
+    if (q % t == 0) return 0;
+  return 1;
+}
+
+/* quadratic character of x modulo the prime q: 0, +1 (a non-zero square) or -1 */
+static int kto_chi(int64_t x, int64_t q) {
+  x %= q;
+  if (x < 0) x += q;
+  if (x == 0) return 0;
+  for (int64_t t = 1; t < q; ++t)
+    if ((t * t) % q == x) return 1;
+  return -1;
+}
+
+/* d = m * p2 as described above; kind 0 Sylvester, 1 Paley I, 2 Paley II.  Returns 0, or -1 when
+ * no construction is found. */
+int kto_hadamard_factor(int64_t d, int64_t *m_out, int64_t *p2_out, int *kind_out) {
+  if (d < 1) return -1;
+  int64_t r = d, t = 0;
+  while ((r & 1) == 0) { r >>= 1; ++t; }
+  if (r == 1) {
+    int64_t m = 1;
+    if (t > 12) { m = (int64_t)1 << (t - 12); if (m < 4) m = 4; }
+    *m_out = m; *p2_out = d / m; *kind_out = 0;
+    return 0;
+  }
+  for (int64_t j = 2; j <= t; ++j) {
+    const int64_t m = r << j;
+    if (m > 256) break;
+    if (kto_is_prime(m - 1)) { *m_out = m; *p2_out = d / m; *kind_out = 1; return 0; }
+    if (kto_is_prime(m / 2 - 1) && (m / 2 - 1) % 4 == 1) { *m_out = m; *p2_out = d / m; *kind_out = 2; return 0; }
+  }
+  return -1;
+}
+
+/* H [m][m] of the given kind (entries +-1) */
+void kto_hadamard_matrix(int64_t m, int kind, int8_t *H) {
+  if (kind == 0) {
+    for (int64_t a = 0; a < m; ++a)
+      for (int64_t b = 0; b < m; ++b) H[a * m + b] = (__builtin_popcountll((unsigned long long)(a & b)) & 1) ? -1 : 1;
+  } else if (kind == 1) {
+    const int64_t q = m - 1;
+    for (int64_t i = 0; i < m; ++i)
+      for (int64_t j = 0; j < m; ++j) {
+        int s;                                   /* entry of S */
+        if (i == 0) s = j == 0 ? 0 : 1;
+        else if (j == 0) s = -1;
+        else s = kto_chi(i - j, q);
+        H[i * m + j] = (int8_t)(s + (i == j ? 1 : 0));
+      }
+  } else {
+    const int64_t h = m / 2, q = h - 1;
+    for (int64_t i = 0; i < m; ++i)
+      for (int64_t j = 0; j < m; ++j) {
+        const int64_t u = i % h, v = j % h;
+        int c;                                   /* entry of C */
+        if (u == v) c = 0;
+        else if (u == 0 || v == 0) c = 1;
+        else c = kto_chi(u - v, q);
+        const int id = u == v ? 1 : 0;
+        int e;
+        if (i < h && j < h) e = c + id;
+        else if (i >= h && j >= h) e = -c - id;
+        else e = c - id;
+        H[i * m + j] = (int8_t)e;
+      }
+  }
+}
+
+/*
+ * Y[i][:] = (X[i][:] * signs) H_d / sqrt(d) with H_d as defined above.  The Sylvester factor is
+ * written out entry by entry: S[a][b] = (-1)^popcount(a & b)  (the closed form of the recursion
+ * S_1 = [1], S_2m = [[S_m, S_m], [S_m, -S_m]]).  signs (d values +-1) may be NULL.
+ * Plain O(d^2) per row: this is the definition, not a fast transform.  Returns 0, or -1 when d
+ * has no construction.
+ */
+int kto_hadamard_rows(const double *X, const double *signs, int64_t n, int64_t d, double *Y) {
+  int64_t m, p2;
+  int kind;
+  if (kto_hadamard_factor(d, &m, &p2, &kind) != 0) return -1;
+  int8_t *H = (int8_t *)malloc((size_t)(m * m));
+  kto_hadamard_matrix(m, kind, H);
   const double sc = 1.0 / sqrt((double)d);
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < n; ++i) {
-    for (int64_t b = 0; b < d; ++b) {
-      double acc = 0.0;
-      for (int64_t a = 0; a < d; ++a) {
-        const double x = X[i * d + a] * (signs ? signs[a] : 1.0);
-        acc += (__builtin_popcountll((unsigned long long)(a & b)) & 1) ? -x : x;
+    for (int64_t ao = 0; ao < m; ++ao)
+      for (int64_t bo = 0; bo < p2; ++bo) {
+        double acc = 0.0;
+        for (int64_t ai = 0; ai < m; ++ai) {
+          const double h = (double)H[ai * m + ao];
+          for (int64_t bi = 0; bi < p2; ++bi) {
+            const int64_t k = ai * p2 + bi;
+            const double x = X[i * d + k] * (signs ? signs[k] : 1.0) * h;
+            acc += (__builtin_popcountll((unsigned long long)(bi & bo)) & 1) ? -x : x;
+          }
+        }
+        Y[i * d + ao * p2 + bo] = acc * sc;
       }
-      Y[i * d + b] = acc * sc;
-    }
   }
+  free(H);
+  return 0;
 }
 
 /*
