@@ -251,12 +251,24 @@ kt_status kt_quant_sensitivity(const float* Y, int64_t count, int32_t bits, cons
 /*
  * The online rotations of "Placement of the Rotations" (R3, R4, R5: random Hadamard matrices
  * applied to activations at run time):  Y[i][:] = (X[i][:] * signs) H_d / sqrt(d) for every
- * token row, H_d the Sylvester-Hadamard matrix (H_1 = [1], H_2m = [[H_m, H_m], [H_m, -H_m]]).
+ * token row.  The paper does not say which Hadamard matrix of order d is meant (any one is a
+ * rotation after scaling); this library uses, for d = r 2^t with r odd,
+ *   H_d = H_m (x) S_{2^k}   (Kronecker product: element a 2^k + b of a row, a < m, b < 2^k),
+ *   S the Sylvester matrix (S_1 = [1], S_2j = [[S_j, S_j], [S_j, -S_j]]),
+ *   r = 1: m = 1 for t <= 12, else m = max(4, 2^(t-12)) and H_m = S_m  (H_d = S_d either way);
+ *   r > 1: m = r 2^j for the smallest j >= 2 with m - 1 prime (Paley's first construction:
+ *          H_m = I + [[0, 1^T], [-1, Q]], Q[u][v] = the quadratic character of u - v modulo
+ *          q = m - 1), else with q = m/2 - 1 prime, q = 1 mod 4 (Paley's second construction:
+ *          C = [[0, 1^T], [1, Q]], H_m = [[C + I, C - I], [C - I, -C - I]]).
+ * This covers the hidden and FFN sizes 2^k, 3, 5, 7, 9, 11, 15, 27 x 2^k (5120, 6144, 13824,
+ * 14336, 28672, ...); 11008 = 43 x 2^8 has no such factor up to order 128 and is refused.
  *  X, Y   [n][ldx], [n][ldy] row-major, `dtype` (KT_BF16: fp32 arithmetic, rounded to nearest
- *         even at the end); Y may be X (in place).  Rows 16-byte aligned.
+ *         even at the end; for m > 1 the result of the S factor passes through Y in bf16 before the
+ *         H_m factor is applied); Y may be X (in place).  Rows 16-byte aligned.
  *  signs  [d] int8 +-1 (the random diagonal of a "random Hadamard" rotation), or NULL.
- *  d      power of two, 128 <= d <= 4096.  Without signs the transform is its own inverse.
- * No workspace.  HBM-bound: one read and one write of the rows.
+ *  d      as above with 128 <= 2^k <= 4096 and m <= 128.  For m = 1 without signs the transform
+ *         is its own inverse.
+ * No workspace.  HBM-bound: one read and one write of the rows per factor.
  */
 kt_status kt_hadamard_rows(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs,
                            int64_t n, int64_t d, kt_dtype dtype, void* stream);

@@ -625,7 +625,7 @@ static kt_status cayley_run(const CayleyPlan& p, char* ws, float* R, const float
 // ------------------------------------------------------------- Hadamard rows ----
 template <typename T, int LOG2D>
 static kt_status launch_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs, int64_t n,
-                                 hipStream_t st) {
+                                 float scale, int sign_rows, hipStream_t st) {
   constexpr size_t lds = 4 * (size_t)kHadRegion * 4;
   static bool attr_done = false;
   if (!attr_done) {
@@ -637,23 +637,103 @@ static kt_status launch_hadamard(const void* X, int64_t ldx, void* Y, int64_t ld
   const int64_t rows = kHadChunk >> LOG2D, chunks = ceil_div(n, rows);
   const int64_t wgs = ceil_div(chunks, 4) < 2 * kNumCUs ? ceil_div(chunks, 4) : 2 * kNumCUs;
   hipLaunchKernelGGL((hadamard_rows_kernel<T, LOG2D>), dim3((unsigned)wgs), dim3(256), lds, st,
-                     static_cast<const T*>(X), ldx, static_cast<T*>(Y), ldy, signs, n,
-                     1.0f / sqrtf((float)(1 << LOG2D)));
+                     static_cast<const T*>(X), ldx, static_cast<T*>(Y), ldy, signs, n, scale, sign_rows);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "Hadamard launch failed");
   return KT_OK;
 }
 
 template <typename T>
 static kt_status dispatch_hadamard(int log2d, const void* X, int64_t ldx, void* Y, int64_t ldy,
-                                   const int8_t* signs, int64_t n, hipStream_t st) {
+                                   const int8_t* signs, int64_t n, float scale, int sign_rows, hipStream_t st) {
   switch (log2d) {
-    case 7: return launch_hadamard<T, 7>(X, ldx, Y, ldy, signs, n, st);
-    case 8: return launch_hadamard<T, 8>(X, ldx, Y, ldy, signs, n, st);
-    case 9: return launch_hadamard<T, 9>(X, ldx, Y, ldy, signs, n, st);
-    case 10: return launch_hadamard<T, 10>(X, ldx, Y, ldy, signs, n, st);
-    case 11: return launch_hadamard<T, 11>(X, ldx, Y, ldy, signs, n, st);
-    default: return launch_hadamard<T, 12>(X, ldx, Y, ldy, signs, n, st);
+    case 7: return launch_hadamard<T, 7>(X, ldx, Y, ldy, signs, n, scale, sign_rows, st);
+    case 8: return launch_hadamard<T, 8>(X, ldx, Y, ldy, signs, n, scale, sign_rows, st);
+    case 9: return launch_hadamard<T, 9>(X, ldx, Y, ldy, signs, n, scale, sign_rows, st);
+    case 10: return launch_hadamard<T, 10>(X, ldx, Y, ldy, signs, n, scale, sign_rows, st);
+    case 11: return launch_hadamard<T, 11>(X, ldx, Y, ldy, signs, n, scale, sign_rows, st);
+    default: return launch_hadamard<T, 12>(X, ldx, Y, ldy, signs, n, scale, sign_rows, st);
   }
+}
+
+static bool is_prime(int64_t q) {
+  if (q < 2) return false;
+  for (int64_t t = 2; t * t <= q; ++t)
+    if (q % t == 0) return false;
+  return true;
+}
+
+// How a row length splits into H_d = H_m (x) S_p2 (stated in kt.h).  kind 0: H_m Sylvester,
+// 1: Paley's first construction, 2: Paley's second.  False when there is no such split.
+static bool hadamard_split(int64_t d, int* m, int* p2, int* kind) {
+  int64_t r = d;
+  int t = 0;
+  while (r > 1 && (r & 1) == 0) { r >>= 1; ++t; }
+  if (r == 1) {
+    int64_t mm = 1;
+    if (t > 12) mm = (int64_t(1) << (t - 12)) < 4 ? 4 : (int64_t(1) << (t - 12));
+    *m = (int)mm; *p2 = (int)(d / mm); *kind = 0;
+    return true;
+  }
+  for (int j = 2; j <= t; ++j) {
+    const int64_t mm = r << j;
+    if (mm > 256) break;
+    const int k = is_prime(mm - 1) ? 1 : (is_prime(mm / 2 - 1) && (mm / 2 - 1) % 4 == 1) ? 2 : 0;
+    if (k) { *m = (int)mm; *p2 = (int)(d / mm); *kind = k; return true; }
+  }
+  return false;
+}
+
+template <typename T>
+static kt_status run_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs, int64_t n,
+                              int64_t d, int m, int p2, int kind, hipStream_t st) {
+  int log2p = 0;
+  while ((1 << log2p) < p2) ++log2p;
+  const float scale = 1.0f / sqrtf((float)d);
+  // the Sylvester factor on the m segments of every row (p2 consecutive elements at a * p2), X -> Y:
+  // contiguous rows are one matrix of n * m short rows; otherwise one launch per segment
+  if (ldx == d && ldy == d && n * m < ((int64_t)1 << 31)) {
+    kt_status s = dispatch_hadamard<T>(log2p, X, p2, Y, p2, signs, n * m, scale, m, st);
+    if (s != KT_OK) return s;
+  } else {
+    for (int a = 0; a < m; ++a) {
+      kt_status s = dispatch_hadamard<T>(log2p, static_cast<const T*>(X) + (int64_t)a * p2, ldx,
+                                         static_cast<T*>(Y) + (int64_t)a * p2, ldy,
+                                         signs ? signs + (int64_t)a * p2 : nullptr, n, scale, 1, st);
+      if (s != KT_OK) return s;
+    }
+  }
+  if (m == 1) return KT_OK;
+  // the order-m factor across the segments, in place on Y
+  const int64_t tiles = n * (p2 / 128);
+  const int64_t wgs = tiles < 8 * kNumCUs ? tiles : 8 * kNumCUs;
+  if (sizeof(T) == 2 && m > 44) {  // bf16, large factor: exact on the matrix cores, where the vector version is ALU-bound
+    const int MB = (m + 31) / 32, KS = (m + 15) / 16;
+    const size_t lds = (size_t)32 * MB * 32 * KS + 2 * (size_t)16 * KS * 256;
+    static size_t attr_lds = 0;
+    if (lds > attr_lds) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_cross_mfma_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
+      attr_lds = lds;
+    }
+    hipLaunchKernelGGL(hadamard_cross_mfma_kernel, dim3((unsigned)wgs), dim3(256), lds, st,
+                       reinterpret_cast<__bf16*>(Y), ldy, n, m, p2, kind);
+  } else {
+    int cgroups = m >= 12 ? 1 : (m == 8 ? 2 : 4);  // as in the kernel
+    while (cgroups > 1 && p2 / 128 < cgroups) cgroups /= 2;
+    const size_t lds = ((size_t)m * m + 128 * (size_t)cgroups * m) * 4 + (size_t)m;
+    static size_t attr_lds = 0;
+    if (lds > attr_lds) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_cross_kernel<T>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
+      attr_lds = lds;
+    }
+    hipLaunchKernelGGL((hadamard_cross_kernel<T>), dim3((unsigned)wgs), dim3(256), lds, st, static_cast<T*>(Y), ldy,
+                       n, m, p2, kind);
+  }
+  if (!launch_ok()) return fail(KT_ERR_DEVICE, "Hadamard factor launch failed");
+  return KT_OK;
 }
 
 extern "C" {
@@ -898,20 +978,21 @@ kt_status kt_hadamard_rows(const void* X, int64_t ldx, void* Y, int64_t ldy, con
   if (!X || !Y) return fail(KT_ERR_INVALID_ARG, "X and Y must not be null");
   if (n < 1) return fail(KT_ERR_INVALID_ARG, "n must be positive");
   if (dtype != KT_F32 && dtype != KT_BF16) return fail(KT_ERR_BAD_DTYPE, "dtype must be KT_F32 or KT_BF16");
-  if (d < 128 || d > 4096 || (d & (d - 1)) != 0)
-    return fail(KT_ERR_BAD_SHAPE, "d = %lld: the Hadamard transform here needs a power of two in [128, 4096]",
+  int m = 0, p2 = 0, kind = 0;
+  if (d < 128 || d > 524288 || !hadamard_split(d, &m, &p2, &kind) || p2 < 128 || p2 > 4096 || m > 128)
+    return fail(KT_ERR_BAD_SHAPE,
+                "d = %lld: the Hadamard transform here needs d = m 2^k with 128 <= 2^k <= 4096 and m = 1, a power "
+                "of two or a Paley order (q + 1 or 2 (q + 1), q prime) up to 128",
                 (long long)d);
   const int64_t vec = dtype == KT_F32 ? 4 : 8;
   if (ldx < d || ldy < d || ldx % vec != 0 || ldy % vec != 0)
     return fail(KT_ERR_BAD_SHAPE, "ldx / ldy must be >= d and keep rows 16-byte aligned");
   if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Y)) & 15)
     return fail(KT_ERR_BAD_SHAPE, "X and Y must be 16-byte aligned");
-  int log2d = 0;
-  while ((int64_t(1) << log2d) < d) ++log2d;
   hipStream_t st = static_cast<hipStream_t>(stream);
   ProfScope prof(5, st);
-  if (dtype == KT_F32) return dispatch_hadamard<float>(log2d, X, ldx, Y, ldy, signs, n, st);
-  return dispatch_hadamard<bf16>(log2d, X, ldx, Y, ldy, signs, n, st);
+  if (dtype == KT_F32) return run_hadamard<float>(X, ldx, Y, ldy, signs, n, d, m, p2, kind, st);
+  return run_hadamard<bf16>(X, ldx, Y, ldy, signs, n, d, m, p2, kind, st);
 }
 
 kt_status kt_fuse_rotation(const float* W, int64_t ldw, const float* R, int64_t ldr, float* Wout, int64_t ldo,
