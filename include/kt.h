@@ -90,7 +90,7 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
  *  R        [batch][d][ldr] row-major, r_dtype.  With bf16 X, R may be the fp32 master
  *           (rounded to bf16, nearest-even, inside) or already bf16; the loss and
  *           gradient are those at the bf16-rounded R.  With fp32 X, R must be fp32.
- *  d        multiple of 128, <= 32768.   1 <= n <= 2^22, any value (tail rows are masked).
+ *  d        multiple of 128, <= 16384.   1 <= n <= 2^22, any value (tail rows are masked).
  *  loss     [batch] fp32, written.
  *  row_kurt [batch][n] fp32 or NULL.
  *  dR       [batch][d][d] fp32 or NULL (NULL: loss only, the backward GEMMs are skipped).

@@ -266,8 +266,8 @@ static kt_status check_xr(const void* X, int64_t ldx, const void* R, int64_t ldr
     return fail(KT_ERR_BAD_DTYPE, "the fp32 path needs an fp32 R");
   if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
   // n is bounded so that 255 rows of a token-minor operand stay inside 32-bit byte offsets
-  if (d > 32768 || n > (int64_t)1 << 22 || batch > 65535)
-    return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 32768, n <= 2^22, batch <= 65535)");
+  if (d > 16384 || n > (int64_t)1 << 22 || batch > 65535)
+    return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 16384, n <= 2^22, batch <= 65535)");
   const int64_t align = xdt == KT_F32 ? 4 : 8;
   if (ldx < d || ldx % align != 0)
     return fail(KT_ERR_BAD_SHAPE, "ldx = %lld must be >= d and a multiple of %lld", (long long)ldx,
@@ -832,7 +832,7 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   if (!R || !dR) return fail(KT_ERR_INVALID_ARG, "R and dR must not be null");
   if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
   if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
-  if (d > 32768 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range");
+  if (d > 16384 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 16384, batch <= 65535)");
   if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
   const CayleyPlan p = plan_cayley(batch, d);
   kt_status s = check_ws(workspace, workspace_bytes, p.total);
@@ -853,7 +853,7 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
   if (!R || !dR || !M || !v) return fail(KT_ERR_INVALID_ARG, "R, dR, M and v must not be null");
   if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
   if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
-  if (d > 32768 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range");
+  if (d > 16384 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 16384, batch <= 65535)");
   if (step < 1) return fail(KT_ERR_INVALID_ARG, "step counts from 1");
   if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
   if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
@@ -1002,7 +1002,7 @@ kt_status kt_fuse_rotation(const float* W, int64_t ldw, const float* R, int64_t 
   if (!W || !R || !Wout) return fail(KT_ERR_INVALID_ARG, "W, R and Wout must not be null");
   if (k < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "k and d must be positive");
   if (side != 0 && side != 1) return fail(KT_ERR_INVALID_ARG, "side must be 0 (W R) or 1 (R^T W)");
-  if (d % 128 != 0 || d > 32768) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128 (<= 32768)", (long long)d);
+  if (d % 128 != 0 || d > 16384) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128 (<= 16384)", (long long)d);
   if (k > (int64_t(1) << 22)) return fail(KT_ERR_BAD_SHAPE, "k out of range");
   const int64_t wcols = side == 0 ? d : k;
   if (ldw < wcols || ldo < wcols || ldr < d || ldw % 4 != 0 || ldo % 4 != 0 || ldr % 4 != 0)

@@ -201,3 +201,85 @@ def test_c3_full_size_pooled_loss():
     oc = oracle.pooled_loss_grad(ktgen.to_f64(X[0, :m]), ktgen.to_f64(ktgen.bf16_round(R[0])))
     assert abs(l2.item() - oc["loss"]) <= 2e-2 * oc["kappa"]
     assert rel_fro(d2[0].cpu().numpy(), oc["dR"]) <= 2e-2
+
+
+# ---- the largest sizes the boundary accepts ---------------------------------------------------------
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (128, "f32"), (256, "bf16")])
+def test_maximum_token_count(d, dtype):
+    """n = 2^22 tokens of one problem (d = 128 bf16: the single-pass kernel; fp32 and d = 256: the
+    three-GEMM path with 1024 token blocks of the token-minor copies).  Sampled rows (the first, the
+    last, random ones) against the oracle, the loss as the mean of the row values, the gradient
+    invariants, and additivity over four quarters; n + 1 is refused."""
+    n = 1 << 22
+    X = ktgen.make_x(n, d, seed=d, outlier_cols=3, outlier_scale=30.0, t_frac=0.01, dtype=dtype,
+                     device="cuda", chunk_rows=1 << 18).unsqueeze(0)
+    R = ktgen.random_orthogonal(d, seed=5, device="cuda").unsqueeze(0)
+    ws = kt.Workspace()
+    rk = torch.empty((1, n), device="cuda")
+    dR = torch.empty((1, d, d), device="cuda")
+    loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    rk_d = rk[0].double()
+    assert abs(loss.item() - float(rk_d.mean())) <= 1e-5 * float(rk_d.mean())
+    rows = np.concatenate([np.arange(40), np.arange(n - 40, n),
+                           np.random.default_rng(2).choice(n, size=60, replace=False)])
+    Ro = ktgen.to_f64(ktgen.bf16_round(R[0]) if dtype == "bf16" else R[0])
+    o = oracle.loss_grad(ktgen.to_f64(X[0, torch.as_tensor(rows, device="cuda")]), Ro, want_dR=False)
+    assert np.max(np.abs(rk_d[torch.as_tensor(rows, device="cuda")].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= tol
+    dR_d = dR[0].double()
+    nrm = float(dR_d.norm())
+    assert float(dR_d.sum(1).norm()) <= 1e-3 * nrm * np.sqrt(d)
+    assert abs(float((dR_d * torch.as_tensor(Ro, device="cuda")).sum())) <= 1e-3 * nrm * np.linalg.norm(Ro)
+    acc = torch.zeros((d, d), dtype=torch.float64, device="cuda")
+    l2 = torch.empty(1, device="cuda")
+    d2 = torch.empty((1, d, d), device="cuda")
+    q = n // 4
+    for c in range(4):
+        kt.kt_kurtosis_loss_grad(X[:, c * q:(c + 1) * q], R, loss=l2, dR=d2, workspace=ws)
+        acc += q * d2[0].double()
+    torch.cuda.synchronize()
+    assert float((n * dR_d - acc).norm()) <= (5e-3 if dtype == "bf16" else 1e-4) * float(acc.norm())
+    with pytest.raises(Exception):
+        kt.kt_kurtosis_loss_grad(torch.empty((1, n + 1, d), dtype=X.dtype, device="cuda"), R, workspace=ws)
+
+
+def test_maximum_hidden_size():
+    """d = 16384, the largest hidden size the boundary accepts: loss and gradient of a few token rows
+    against the oracle at that d, and a Cayley step against the framework's fp64 solve (as for
+    d = 8192 above); d = 16384 + 128 is refused."""
+    d, n, lr = 16384, 16, 1e-2
+    g = torch.Generator(device="cuda").manual_seed(11)
+    q, r = torch.linalg.qr(torch.randn((d, d), generator=g, device="cuda"))
+    R = (q * torch.sign(torch.diagonal(r)).unsqueeze(0)).contiguous().unsqueeze(0)
+    del q, r
+    X = ktgen.make_x(n, d, seed=3, outlier_cols=16, outlier_scale=50.0, t_frac=0.02, dtype="bf16", device="cuda").unsqueeze(0)
+    ws = kt.Workspace()
+    rk = torch.empty((1, n), device="cuda")
+    dR = torch.empty((1, d, d), device="cuda")
+    loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    o = oracle.loss_grad(ktgen.to_f64(X[0]), ktgen.to_f64(ktgen.bf16_round(R[0])))
+    assert abs(loss.item() - o["loss"]) <= 2e-2 * o["loss"]
+    assert np.max(np.abs(rk[0].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= 2e-2
+    assert rel_fro(dR[0].cpu().numpy(), o["dR"]) <= 2e-2
+    del o
+    Rn = R.clone()
+    oe = torch.zeros(1, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    G = torch.randn((1, d, d), generator=g, device="cuda") / np.sqrt(d)   # as in the d = 8192 test above
+    kt.kt_cayley_step(Rn, G, lr, ortho_err=oe, info=info, workspace=ws)
+    torch.cuda.synchronize()
+    Rd, Gd = R[0].double(), G[0].double()
+    A = Gd @ Rd.T - Rd @ Gd.T
+    I = torch.eye(d, dtype=torch.float64, device="cuda")
+    ref = torch.linalg.solve(I + 0.5 * lr * A, (I - 0.5 * lr * A) @ Rd)
+    step = ref - Rd
+    # the fixed point stops at an ABSOLUTE change per entry (3e-7, the scale of the orthogonality bound);
+    # the entries of a step shrink like 1/sqrt(d), so relative to the step that is ~1e-4 at this size
+    assert float((Rn[0].double() - Rd - step).norm() / step.norm()) <= 3e-4
+    assert 1 <= info.item() <= 32 and oe.item() < 1e-6
+    del A, ref, step
+    with pytest.raises(Exception):
+        kt.kt_kurtosis_loss_grad(torch.zeros((1, 4, d + 128), dtype=torch.bfloat16, device="cuda"),
+                                 torch.zeros((1, d + 128, d + 128), device="cuda"))
