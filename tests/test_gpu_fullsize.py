@@ -283,3 +283,35 @@ def test_maximum_hidden_size():
     with pytest.raises(Exception):
         kt.kt_kurtosis_loss_grad(torch.zeros((1, 4, d + 128), dtype=torch.bfloat16, device="cuda"),
                                  torch.zeros((1, d + 128, d + 128), device="cuda"))
+
+
+def test_maximum_problem_count():
+    """batch = 65535 independent d = 128 problems of 64 tokens (the largest grid the batched kernels are
+    launched with): loss, gradient and Cayley step of the first, a middle and the last problem against
+    the oracle; batch + 1 is refused."""
+    batch, n, d, lr = 65535, 64, 128, 1e-2
+    X = ktgen.make_x(batch * n, d, seed=9, base="t4", outlier_cols=2, outlier_scale=8.0, dtype="bf16",
+                     device="cuda", chunk_rows=1 << 18).reshape(batch, n, d)
+    R1 = torch.stack([ktgen.random_orthogonal(d, seed=s) for s in range(3)]).cuda()
+    R = R1[torch.arange(batch, device="cuda") % 3].contiguous()
+    ws = kt.Workspace()
+    dR = torch.empty((batch, d, d), device="cuda")
+    rk = torch.empty((batch, n), device="cuda")
+    loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
+    Rn = R.clone()
+    oe = torch.zeros(batch, device="cuda")
+    info = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    kt.kt_cayley_step(Rn, dR, lr, ortho_err=oe, info=info, workspace=ws)
+    torch.cuda.synchronize()
+    assert float(oe.max()) < 1e-6 and int(info.min()) >= 1
+    for p in (0, 32767, batch - 1):
+        Ro = ktgen.to_f64(ktgen.bf16_round(R[p]))
+        o = oracle.loss_grad(ktgen.to_f64(X[p]), Ro)
+        assert abs(loss[p].item() - o["loss"]) <= 2e-2 * o["loss"], p
+        assert np.max(np.abs(rk[p].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= 2e-2, p
+        assert rel_fro(dR[p].cpu().numpy(), o["dR"]) <= 2e-2, p
+        ref = oracle.cayley_step(ktgen.to_f64(R[p]), dR[p].cpu().double().numpy(), lr)
+        stepn = np.linalg.norm(ref - ktgen.to_f64(R[p]))
+        assert np.linalg.norm(Rn[p].cpu().double().numpy() - ref) <= 1e-3 * stepn, p
+    with pytest.raises(Exception):
+        kt.kt_cayley_step(torch.empty((batch + 1, d, d), device="cuda"), torch.empty((batch + 1, d, d), device="cuda"), lr)
