@@ -5,6 +5,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "../../include/kt.h"
 #include "kt_aux.h"
@@ -26,6 +28,26 @@ static kt_status fail(kt_status code, const char* fmt, ...) {
 }
 
 static bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+// Kernels that use more than 64 KiB of dynamic LDS need the limit raised once per kernel AND per
+// device (the attribute belongs to the device's copy of the code).  Remembers what has been set;
+// safe to call from several host threads.
+static bool ensure_dynamic_lds(const void* kernel, size_t bytes) {
+  struct Entry { const void* kernel; int device; size_t bytes; };
+  static std::mutex mu;
+  static std::vector<Entry> done;
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return false;
+  std::lock_guard<std::mutex> lock(mu);
+  Entry* hit = nullptr;
+  for (Entry& e : done)
+    if (e.kernel == kernel && e.device == device) hit = &e;
+  if (hit && hit->bytes >= bytes) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+  if (hit) hit->bytes = bytes;
+  else done.push_back({kernel, device, bytes});
+  return true;
+}
 
 // ------------------------------------------------------------------ profiling -----
 // Optional event brackets around the large launches (see kt_profile_enable).
@@ -73,14 +95,8 @@ static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const vo
                         int64_t bsb, int N, int64_t K, int slabs_per_split, int batch,
                         const Epi& epi, hipStream_t stream, int64_t k_block = 0,
                         int64_t block_stride_a = 0, int64_t block_stride_b = 0) {
-  static bool attr_done = false;
   auto kern = gemm_nt_kernel<TL, Epi>;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES) != hipSuccess)
-      return false;
-    attr_done = true;
-  }
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), TL::LDS_BYTES)) return false;
   GemmShape g;
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb;
   g.batch_stride_a = bsa; g.batch_stride_b = bsb;
@@ -407,13 +423,8 @@ static kt_status run_loss_grad_fused(const LossGradPlan& p, const void* X, int64
                                      int64_t ldr, kt_dtype rdt, int64_t batch, int64_t n, int64_t d,
                                      float kappa_target, float* loss, float* row_kurt, float* dR,
                                      char* ws, hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fused_d128_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kF128LdsBytes) != hipSuccess)
-      return fail(KT_ERR_DEVICE, "the fused d=128 kernel needs %d bytes of LDS per workgroup", kF128LdsBytes);
-    attr_done = true;
-  }
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(fused_d128_kernel), kF128LdsBytes))
+    return fail(KT_ERR_DEVICE, "the fused d=128 kernel needs %d bytes of LDS per workgroup", kF128LdsBytes);
   bf16* RT = reinterpret_cast<bf16*>(ws + p.o_rt);
   double* loss_part = reinterpret_cast<double*>(ws + p.o_losspart);
   float* dR_part = reinterpret_cast<float*>(ws + p.o_splitk);
@@ -488,13 +499,8 @@ using namespace kt;
 template <bool ADAM>
 static kt_status launch_cayley_d128(float* R, const float* G, void* R_lowp, int64_t batch, float half_coef,
                                     float* ortho_err, int32_t* info, const C128Adam& ad, hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(cayley_d128_kernel<ADAM>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kC128LdsBytes) != hipSuccess)
-      return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
-    attr_done = true;
-  }
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(cayley_d128_kernel<ADAM>), kC128LdsBytes))
+    return fail(KT_ERR_DEVICE, "the d=128 Cayley kernel needs %d bytes of LDS per workgroup", kC128LdsBytes);
   hipLaunchKernelGGL(cayley_d128_kernel<ADAM>, dim3((unsigned)batch), dim3(256), kC128LdsBytes, st, R, G,
                      static_cast<__bf16*>(R_lowp), half_coef, ortho_err, info, kCayleyMaxIters, kCayleyTol, ad);
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "Cayley d=128 launch failed");
@@ -627,13 +633,8 @@ template <typename T, int LOG2D>
 static kt_status launch_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, const int8_t* signs, int64_t n,
                                  float scale, int sign_rows, hipStream_t st) {
   constexpr size_t lds = 4 * (size_t)kHadRegion * 4;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_rows_kernel<T, LOG2D>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return fail(KT_ERR_DEVICE, "the Hadamard kernel needs %d bytes of LDS per workgroup", (int)lds);
-    attr_done = true;
-  }
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(hadamard_rows_kernel<T, LOG2D>), lds))
+    return fail(KT_ERR_DEVICE, "the Hadamard kernel needs %d bytes of LDS per workgroup", (int)lds);
   const int64_t rows = kHadChunk >> LOG2D, chunks = ceil_div(n, rows);
   const int64_t wgs = ceil_div(chunks, 4) < 2 * kNumCUs ? ceil_div(chunks, 4) : 2 * kNumCUs;
   hipLaunchKernelGGL((hadamard_rows_kernel<T, LOG2D>), dim3((unsigned)wgs), dim3(256), lds, st,
@@ -709,26 +710,16 @@ static kt_status run_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, 
   if (sizeof(T) == 2 && m > 44) {  // bf16, large factor: exact on the matrix cores, where the vector version is ALU-bound
     const int MB = (m + 31) / 32, KS = (m + 15) / 16;
     const size_t lds = (size_t)32 * MB * 32 * KS + 2 * (size_t)16 * KS * 256;
-    static size_t attr_lds = 0;
-    if (lds > attr_lds) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_cross_mfma_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
-      attr_lds = lds;
-    }
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(hadamard_cross_mfma_kernel), lds))
+      return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
     hipLaunchKernelGGL(hadamard_cross_mfma_kernel, dim3((unsigned)wgs), dim3(256), lds, st,
                        reinterpret_cast<__bf16*>(Y), ldy, n, m, p2, kind);
   } else {
     int cgroups = m >= 12 ? 1 : (m == 8 ? 2 : 4);  // as in the kernel
     while (cgroups > 1 && p2 / 128 < cgroups) cgroups /= 2;
     const size_t lds = ((size_t)m * m + 128 * (size_t)cgroups * m) * 4 + (size_t)m;
-    static size_t attr_lds = 0;
-    if (lds > attr_lds) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_cross_kernel<T>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
-      attr_lds = lds;
-    }
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(hadamard_cross_kernel<T>), lds))
+      return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
     hipLaunchKernelGGL((hadamard_cross_kernel<T>), dim3((unsigned)wgs), dim3(256), lds, st, static_cast<T*>(Y), ldy,
                        n, m, p2, kind);
   }
