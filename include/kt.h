@@ -86,7 +86,7 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
  * as the token-minor scratch operand of the last GEMM.
  *
  *  X        [batch][n][ldx] row-major, x_dtype (KT_BF16, or KT_F32 for the fp32 path);
- *           ldx >= d, rows 16-byte aligned (ldx % 8 == 0 for bf16, % 4 for fp32).
+ *           d <= ldx <= 2^22, rows 16-byte aligned (ldx % 8 == 0 for bf16, % 4 for fp32).
  *  R        [batch][d][ldr] row-major, r_dtype.  With bf16 X, R may be the fp32 master
  *           (rounded to bf16, nearest-even, inside) or already bf16; the loss and
  *           gradient are those at the bf16-rounded R.  With fp32 X, R must be fp32.

@@ -96,6 +96,10 @@ static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const vo
                         const Epi& epi, hipStream_t stream, int64_t k_block = 0,
                         int64_t block_stride_a = 0, int64_t block_stride_b = 0) {
   auto kern = gemm_nt_kernel<TL, Epi>;
+  // the kernel addresses the rows of a tile with 32-bit byte offsets from the tile's first row
+  const int64_t esz = (int64_t)sizeof(typename TL::T);
+  if ((TL::BM - 1) * lda * esz + 128 > (int64_t)UINT32_MAX || (TL::BN - 1) * ldb * esz + 128 > (int64_t)UINT32_MAX)
+    return false;
   if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), TL::LDS_BYTES)) return false;
   GemmShape g;
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb;
@@ -289,6 +293,9 @@ static kt_status check_xr(const void* X, int64_t ldx, const void* R, int64_t ldr
     return fail(KT_ERR_BAD_SHAPE, "ldx = %lld must be >= d and a multiple of %lld", (long long)ldx,
                 (long long)align);
   if (ldr < d) return fail(KT_ERR_BAD_SHAPE, "ldr = %lld must be >= d", (long long)ldr);
+  // 255 rows of X must stay inside 32-bit byte offsets (tiles are addressed from their first row)
+  if (ldx > (int64_t)1 << 22 || ldr > (int64_t)1 << 22)
+    return fail(KT_ERR_BAD_SHAPE, "ldx and ldr must not exceed 2^22 elements");
   if ((reinterpret_cast<uintptr_t>(X) & 15) != 0)
     return fail(KT_ERR_BAD_SHAPE, "X must be 16-byte aligned");
   return KT_OK;

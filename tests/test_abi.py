@@ -82,6 +82,13 @@ def test_argument_errors_are_synchronous():
     assert st == 1 and "clip" in kt.kt_last_error()
     st = L.kt_rotate_fakequant_int4(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.0, None, None, None, None, ws, 1 << 30, None)
     assert st == 1
+    # sizes beyond the documented limits
+    st = L.kt_kurtosis_loss_grad(fake, 16512, fake, 16512, 1, 16, 16512, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 2 and "16384" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, (1 << 22) + 8, fake, 128, 1, 16, 128, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 2 and "2^22" in kt.kt_last_error()
+    st = L.kt_kurtosis_loss_grad(fake, 128, fake, 128, 1, (1 << 22) + 1, 128, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
+    assert st == 2
     # a good call clears the text only when it runs; bad ones leave their own message
     assert kt.kt_last_error() != ""
 
