@@ -142,8 +142,8 @@ kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R
  * clamp is applied: the caller chooses lr.  For d >= 1024 the d^3 products run on the
  * bf16 matrix cores as three-term bf16 products (about 2^-17 relative per term).
  *
- *  R        [batch][d][d] fp32, in/out (master copy).  d multiple of 128.
- *  dR       [batch][d][d] fp32.
+ *  R        [batch][d][d] fp32, in/out (master copy).  d multiple of 128, <= 16384.
+ *  dR       [batch][d][d] fp32.  R and dR 16-byte aligned.
  *  R_lowp   [batch][d][d] bf16 copy of the new R (nearest-even), or NULL.
  *  ortho_err[batch] fp32: max_ij |(R+^T R+ - I)_ij| of the result, or NULL (skips one GEMM).
  *  info     [batch] int32: number of iterations used, or -1 if the iteration did not
@@ -168,8 +168,8 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
  *   a   = min(lr, 2 q / (||W||_F + eps))                keeps the iteration below contractive
  *   R+  = (I + a/2 W)^-1 (I - a/2 W) R                  fixed point Z <- R - (a/2) W (R + Z)
  *
- *  R        [batch][d][d] fp32, in/out.  d multiple of 128.
- *  dR       [batch][d][d] fp32.
+ *  R        [batch][d][d] fp32, in/out.  d multiple of 128, <= 16384.
+ *  dR       [batch][d][d] fp32.  R, dR and M 16-byte aligned.
  *  M        [batch][d][d] fp32 momentum, in/out (zeros before the first step).
  *  v        [batch] fp32 second moment, in/out (1 before the first step).
  *  R_lowp, ortho_err, info: as for kt_cayley_step.

@@ -828,6 +828,8 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
                          void* stream) {
   g_err[0] = 0;
   if (!R || !dR) return fail(KT_ERR_INVALID_ARG, "R and dR must not be null");
+  if ((reinterpret_cast<uintptr_t>(R) | reinterpret_cast<uintptr_t>(dR)) & 15)
+    return fail(KT_ERR_BAD_SHAPE, "R and dR must be 16-byte aligned");
   if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
   if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
   if (d > 16384 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 16384, batch <= 65535)");
@@ -849,6 +851,8 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
                               size_t workspace_bytes, void* stream) {
   g_err[0] = 0;
   if (!R || !dR || !M || !v) return fail(KT_ERR_INVALID_ARG, "R, dR, M and v must not be null");
+  if ((reinterpret_cast<uintptr_t>(R) | reinterpret_cast<uintptr_t>(dR) | reinterpret_cast<uintptr_t>(M)) & 15)
+    return fail(KT_ERR_BAD_SHAPE, "R, dR and M must be 16-byte aligned");
   if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
   if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
   if (d > 16384 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 16384, batch <= 65535)");
