@@ -86,6 +86,7 @@ constexpr int kNumCUs = 256;
 // feature row is contiguous, blocks follow each other feature-row-set by feature-row-set, so
 // the 256 rows a tile streams together span 2 MiB per block instead of one page per row.
 constexpr int64_t kTokenBlock = 4096;
+constexpr int kHadMfmaFrom = 44;  // bf16 Hadamard factors of at least this order run on the matrix cores (measured: the vector kernel wins below)
 constexpr int kSensBlocks = 1024;  // workgroups of the sensitivity sweeps
 constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
@@ -714,13 +715,17 @@ static kt_status run_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, 
   // the order-m factor across the segments, in place on Y
   const int64_t tiles = n * (p2 / 128);
   const int64_t wgs = tiles < 8 * kNumCUs ? tiles : 8 * kNumCUs;
-  if (sizeof(T) == 2 && m > 44) {  // bf16, large factor: exact on the matrix cores, where the vector version is ALU-bound
+  if (sizeof(T) == 2 && m >= kHadMfmaFrom) {  // bf16: exact on the matrix cores
     const int MB = (m + 31) / 32, KS = (m + 15) / 16;
-    const size_t lds = (size_t)32 * MB * 32 * KS + 2 * (size_t)16 * KS * 256;
+    int lognb = 0;  // blocks of 32 columns per wave: as many as keep m * NBW <= 128, fit the segment and 64 KiB of LDS
+    while ((2 << lognb) * m <= 128 && (256 << lognb) <= p2 && 2 * 16 * KS * (512 << lognb) <= 65536) ++lognb;
+    const size_t lds = (size_t)32 * MB * 32 * KS + 2 * (size_t)16 * KS * (256 << lognb);
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(hadamard_cross_mfma_kernel), lds))
       return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
-    hipLaunchKernelGGL(hadamard_cross_mfma_kernel, dim3((unsigned)wgs), dim3(256), lds, st,
-                       reinterpret_cast<__bf16*>(Y), ldy, n, m, p2, kind);
+    const int64_t tiles_m = n * (p2 / (128 << lognb));
+    const int64_t wgs_m = tiles_m < 8 * kNumCUs ? tiles_m : 8 * kNumCUs;
+    hipLaunchKernelGGL(hadamard_cross_mfma_kernel, dim3((unsigned)wgs_m), dim3(256), lds, st,
+                       reinterpret_cast<__bf16*>(Y), ldy, n, m, p2, kind, lognb);
   } else {
     int cgroups = m >= 12 ? 1 : (m == 8 ? 2 : 4);  // as in the kernel
     while (cgroups > 1 && p2 / 128 < cgroups) cgroups /= 2;

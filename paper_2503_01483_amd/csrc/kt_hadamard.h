@@ -273,22 +273,25 @@ __global__ __launch_bounds__(256) void hadamard_cross_kernel(T* __restrict__ Y, 
 }
 
 // The same factor for bf16 rows on the matrix cores: entries +-1 and bf16 inputs make every product
-// exact, the sums run in fp32 as in the vector version.  Per tile of 128 columns of one row:
+// exact, the sums run in fp32 as in the vector version.  Per tile of 128 NBW columns of one row
+// (NBW = 2^lognb blocks of 32 columns per wave, chosen so that a tile holds about 128 x 128 values):
 //   Y_tile[a][c] = sum_a' H_m[a'][a] x[a'][c]   =   A (M = a, K = a') times B (K = a', N = c)
 // A = H_m^T sits in LDS as bf16, K-minor, zero-padded to 32-row blocks and 16-wide K steps, and is
-// read as ordinary 16-byte fragments.  The x tile sits in LDS as loaded (row a' = 256 bytes of 128
-// columns); its fragments (8 consecutive a' of one column per lane) come from the transposing read
-// ds_read_b64_tr_b16.  Rows a' >= m of the tile are zero and never written.  A wave owns 32
-// columns; results go through LDS once more so that the stores are whole 256-byte row pieces.
-// LDS bytes: 32 MB * 32 KS (A) + 2 * 16 KS * 256 (x tile, y tile), MB = ceil(m/32), KS = ceil(m/16).
+// read as ordinary 16-byte fragments.  The x tile sits in LDS as loaded (row a' = the tile's columns);
+// its fragments (8 consecutive a' of one column per lane) come from the transposing read
+// ds_read_b64_tr_b16.  Rows a' >= m of the tile are zero and never written.  Results go through
+// LDS once more so that the stores are whole row pieces; the loads of the next tile are in flight
+// while a tile is worked on.  m NBW <= 128.
+// LDS bytes: 32 MB * 32 KS (A) + 2 * 16 KS * 256 NBW (x tile, y tile), MB = ceil(m/32), KS = ceil(m/16).
 __global__ __launch_bounds__(256) void hadamard_cross_mfma_kernel(__bf16* __restrict__ Y, int64_t ldy, int64_t n,
-                                                                  int m, int p2, int kind) {
+                                                                  int m, int p2, int kind, int lognb) {
   extern __shared__ __align__(16) char cross_raw[];
   const int MB = (m + 31) >> 5, KS = (m + 15) >> 4;
+  const int NBW = 1 << lognb, rowb = 256 << lognb, tcols = 128 << lognb;
   const int a_stride = 32 * KS;  // bytes per row of A: 16 KS bf16
   char* A = cross_raw;
   char* xt = A + 32 * MB * a_stride;
-  char* yt = xt + 16 * KS * 256;
+  char* yt = xt + 16 * KS * rowb;
   unsigned char* isq = reinterpret_cast<unsigned char*>(yt);  // scratch during set-up only
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, l32 = lane & 31;
@@ -330,54 +333,78 @@ __global__ __launch_bounds__(256) void hadamard_cross_mfma_kernel(__bf16* __rest
     reinterpret_cast<__bf16*>(A)[idx] = (__bf16)e;
   }
   __syncthreads();  // isq (inside yt) is free again
-  for (int i = tid; i < 16 * KS * 16; i += 256) reinterpret_cast<intx4*>(xt)[i] = intx4{0, 0, 0, 0};
+  for (int i = tid; i < KS * rowb; i += 256) reinterpret_cast<intx4*>(xt)[i] = intx4{0, 0, 0, 0};
   __syncthreads();
 
-  // lane constants of the transposing reads: column 32 wave + tr_col .. +3 of row 16 s + tr_row (+4)
+  // lane constants of the transposing reads: columns tr_col .. +3 of a 32-column block, row 16 s + tr_row (+4)
   const int g16 = lane >> 4, rr = lane & 15;
   const int tr_col = 16 * (g16 & 1) + 4 * (rr & 3);
   const int tr_row = 8 * (g16 >> 1) + (rr >> 2);
-  const int tr_lo = tr_row * 256 + (32 * wave + tr_col) * 2, tr_hi = tr_lo + 4 * 256;
-  const int ncb = p2 >> 7;
+  const int ncb = p2 / tcols;
   const int64_t tiles = n * ncb;
-  const int lrow = tid >> 4, lchunk = tid & 15;  // tile movement: 16 rows of 16 chunks per pass
+  // tile movement: 16-byte chunk c = tid + 256 i of the tile: row a = c / (16 NBW), chunk c % (16 NBW)
+  const int chunk_shift = 4 + lognb, chunk_mask = (16 << lognb) - 1;
+  intx4 nxt[8];
+  auto request = [&](int64_t tile) __attribute__((always_inline)) {
+    const int64_t row = tile / ncb;
+    const int cb = (int)(tile - row * ncb);
+    const __bf16* src = Y + row * ldy + (int64_t)cb * tcols;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int c = tid + 256 * i, a = c >> chunk_shift;
+      if (tile < tiles && a < m) nxt[i] = *reinterpret_cast<const intx4*>(src + (int64_t)a * p2 + (c & chunk_mask) * 8);
+    }
+  };
+  request(blockIdx.x);
   for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const int64_t row = tile / ncb;
     const int cb = (int)(tile - row * ncb);
-    __bf16* base = Y + row * ldy + cb * 128;
-    for (int a = lrow; a < m; a += 16)
-      *reinterpret_cast<intx4*>(xt + a * 256 + lchunk * 16) =
-          *reinterpret_cast<const intx4*>(base + (int64_t)a * p2 + lchunk * 8);
+    __bf16* base = Y + row * ldy + (int64_t)cb * tcols;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int c = tid + 256 * i, a = c >> chunk_shift;
+      if (a < m) *reinterpret_cast<intx4*>(xt + a * rowb + (c & chunk_mask) * 16) = nxt[i];
+    }
+    request(tile + gridDim.x);
     __syncthreads();
-    floatx16 acc[4];
+    for (int nb = 0; nb < NBW; ++nb) {
+      const int col0 = (wave * NBW + nb) * 32;  // this wave's block of 32 columns
+      const int tr_lo = tr_row * rowb + (col0 + tr_col) * 2, tr_hi = tr_lo + 4 * rowb;
+      floatx16 acc[4];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
-    for (int s = 0; s < KS; ++s) {
-      const intx4 bf = read_tr_operand(xt, tr_lo + s * 16 * 256, tr_hi + s * 16 * 256);
+        for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+      for (int s = 0; s < KS; ++s) {
+        const intx4 bf = read_tr_operand(xt, tr_lo + s * 16 * rowb, tr_hi + s * 16 * rowb);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+          if (mb < MB) {
+            const intx4 af = *reinterpret_cast<const intx4*>(A + (32 * mb + l32) * a_stride + (2 * s + half) * 16);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af),
+                                                              __builtin_bit_cast(bf16x8, bf), acc[mb], 0, 0, 0);
+          }
+      }
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
         if (mb < MB) {
-          const intx4 af = *reinterpret_cast<const intx4*>(A + (32 * mb + l32) * a_stride + (2 * s + half) * 16);
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af),
-                                                            __builtin_bit_cast(bf16x8, bf), acc[mb], 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int a = 32 * mb + ((r >> 2) << 3) + (half << 2) + (r & 3);
+            if (a < m) reinterpret_cast<__bf16*>(yt)[a * tcols + col0 + l32] = (__bf16)acc[mb][r];
+          }
         }
     }
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-      if (mb < MB) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int a = 32 * mb + ((r >> 2) << 3) + (half << 2) + (r & 3);
-          if (a < m) reinterpret_cast<__bf16*>(yt)[a * 128 + 32 * wave + l32] = (__bf16)acc[mb][r];
-        }
-      }
     __syncthreads();
-    for (int a = lrow; a < m; a += 16)
-      *reinterpret_cast<intx4*>(base + (int64_t)a * p2 + lchunk * 8) =
-          *reinterpret_cast<const intx4*>(yt + a * 256 + lchunk * 16);
-    // the next tile's loads touch xt only, its stores to yt come after the next barrier
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int c = tid + 256 * i, a = c >> chunk_shift;
+      if (a < m)
+        *reinterpret_cast<intx4*>(base + (int64_t)a * p2 + (c & chunk_mask) * 8) =
+            *reinterpret_cast<const intx4*>(yt + a * rowb + (c & chunk_mask) * 16);
+    }
+    // the next tile's stores to xt come after every wave has passed the barrier above (its reads of
+    // xt are done), its stores to yt after the next barrier (the copy-out above is done)
   }
 }
 
