@@ -90,6 +90,7 @@ constexpr int kHadMfmaFrom = 44;  // bf16 Hadamard factors of at least this orde
 constexpr int kSensBlocks = 1024;  // workgroups of the sensitivity sweeps
 constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
+constexpr int kCayleyFusedFrom = 6;  // three-term path: iterations from here on are single launches
 
 template <class TL, class Epi>
 static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const void* B, int64_t ldb,
@@ -576,8 +577,26 @@ static kt_status cayley_run(const CayleyPlan& p, char* ws, float* R, const float
       // cross terms come out whichever operand carries which layout
       if (!product(Bs, Us[0], 0, adam->M, 0.5f)) return fail(KT_ERR_DEVICE, "momentum projection GEMM launch failed");
     }
-    const unsigned ub = (unsigned)(ceil_div(dd / 4, 256) < 2048 ? ceil_div(dd / 4, 256) : 2048);
+    const unsigned ub = (unsigned)(ceil_div(dd / 4, 256) < 512 ? ceil_div(dd / 4, 256) : 512);
+    // The first iterations run as product + elementwise update (the faster pair when they do real
+    // work); the later ones, which almost always only find the convergence flag set, as ONE launch
+    // each with the update in the GEMM epilogue: half as many launches to skip through.
+    auto fused_iteration = [&](int it) -> bool {
+      auto go = [&](auto tile_tag) -> bool {
+        using TL = decltype(tile_tag);
+        EpiCayleyIter<TL> e;
+        e.Rt = Rt; e.Zt = Zt; e.Unew = nullptr; e.Usplit = Us[(it + 1) & 1]; e.delta = delta;
+        e.d = D; e.it = it; e.max_iters = kCayleyMaxIters; e.tol = kCayleyTol;
+        e.bscale = adam ? adam->scal : nullptr;
+        return launch_gemm<TL>(Us[it & 1], 3 * d, sd, D, Bs, 3 * d, sd, D, 3 * d, 0, (int)batch, e, st);
+      };
+      return big ? go(TB_BIG{}) : go(TB_128{});
+    };
     for (int it = 0; it < kCayleyMaxIters; ++it) {
+      if (it >= kCayleyFusedFrom) {
+        if (!fused_iteration(it)) return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
+        continue;
+      }
       if (!product(Us[it & 1], Bs, it)) return fail(KT_ERR_DEVICE, "Cayley iteration launch failed");
       hipLaunchKernelGGL(cayley_update_kernel, dim3(ub, (unsigned)batch), dim3(256), 0, st, Mm, Rt, Zt,
                          Us[(it + 1) & 1], D, delta, it, kCayleyMaxIters, kCayleyTol, adam ? adam->scal : nullptr);

@@ -62,6 +62,24 @@ def test_clamp_engages_for_a_huge_learning_rate():
     assert 1 <= info[0] <= 32 and oe[0] < 1e-6
 
 
+def test_low_rank_step_at_the_clamp_needs_many_iterations():
+    # a rank-one gradient makes ||W||_2 ~ ||W||_F / sqrt(2): with the clamp engaged the fixed point contracts
+    # by ~0.35 per iteration, long enough to reach the single-launch form of the late iterations (d >= 1024)
+    d = 1024
+    g = torch.Generator().manual_seed(5)
+    R = ktgen.random_orthogonal(d, seed=6).unsqueeze(0)
+    u, w = torch.randn(d, generator=g), torch.randn(d, generator=g)
+    G = (torch.outer(u, w) / d).unsqueeze(0)
+    M, v = torch.zeros(1, d, d), torch.ones(1)
+    Rn, Mn, vn, lowp, oe, info, sc = _gpu_step(R, G, M, v, 1, 1e3)
+    o = oracle.cayley_adam_step(ktgen.to_f64(R[0]), ktgen.to_f64(G[0]), ktgen.to_f64(M[0]), 1.0, 1, F(1e3), **HP)
+    assert abs(sc[0, 1] * sc[0, 2] - 1.0) < 1e-4 and 6 < info[0] <= 32
+    step = o["R"] - ktgen.to_f64(R[0])
+    assert rel_fro(Rn[0].numpy().astype(np.float64) - ktgen.to_f64(R[0]), step) <= 1e-4
+    assert rel_fro(Mn[0].numpy().astype(np.float64), o["M"]) <= 1e-4
+    assert oe[0] < 1e-6
+
+
 def test_zero_gradient_and_momentum_leave_r_unchanged():
     d = 256
     R = ktgen.random_orthogonal(d, seed=3).unsqueeze(0)
