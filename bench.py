@@ -26,7 +26,7 @@ KERNEL_NAMES = {0: "gemm_nt_kernel<bf16 256x256, EpiMoments> (forward + row mome
 # Fabric-side bytes per launch (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, calibrated on a 1 GiB
 # device copy; see profiles/c3_gemm_counters.md).  Counters need a profiler run of their own, so the
 # figures measured for the default workload are carried here as constants; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {"C3": {0: (6.00 + 0.0625) * 2**30, 1: (6.01 + 1.0) * 2**30, 2: (11.8 + 0.0625) * 2**30}}
+MEASURED_TRAFFIC_BYTES = {"C3": {0: (6.00 + 0.0625) * 2**30, 1: (6.01 + 1.0) * 2**30, 2: (6.00 + 0.0625) * 2**30}}
 CPU_SAMPLE_ROWS = {"C1": 2048, "C2": 32768, "C3": 16384, "C4": 131072, "C5": 4096}
 
 

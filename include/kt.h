@@ -83,7 +83,8 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
  *
  * Y and dL/dY as such never reach HBM in row-major form: Y is consumed in the GEMM
  * epilogue (row moments), recomputed for the backward pass, and dL/dY is kept only
- * as the token-minor scratch operand of the last GEMM.
+ * as the token-minor scratch operand of the last GEMM (which reads X itself in place when
+ * X is bf16 and d a multiple of 256, through a token-minor copy otherwise).
  *
  *  X        [batch][n][ldx] row-major, x_dtype (KT_BF16, or KT_F32 for the fp32 path);
  *           d <= ldx <= 2^22, rows 16-byte aligned (ldx % 8 == 0 for bf16, % 4 for fp32).
@@ -295,7 +296,8 @@ kt_status kt_fuse_rotation(const float* W, int64_t ldw, const float* R, int64_t 
  * only process-global state the library has; enable/disable/read are host calls and
  * must not run concurrently with other library calls.
  *   kernel ids: 0 forward GEMM + row moments, 1 backward recompute GEMM + dL/dY,
- *               2 gradient GEMM X^T G, 3 token-minor copy of X,
+ *               2 gradient GEMM X^T G, 3 token-minor copy of X (fp32, or d not a multiple of 256: bf16 with
+ *               d % 256 == 0 reads X as it is),
  *               4 every launch of kt_cayley_step, 5 every launch of kt_rotate_fakequant_int4
  * kt_profile_enable(max_records): records up to max_records bracketed launches (0 turns
  *   profiling off and releases the events).

@@ -92,17 +92,20 @@ constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
 constexpr int kCayleyFusedFrom = 6;  // three-term path: iterations from here on are single launches
 
-template <class TL, class Epi>
+template <class TL, class Epi, bool ATN = false>
 static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const void* B, int64_t ldb,
                         int64_t bsb, int N, int64_t K, int slabs_per_split, int batch,
                         const Epi& epi, hipStream_t stream, int64_t k_block = 0,
-                        int64_t block_stride_a = 0, int64_t block_stride_b = 0) {
-  auto kern = gemm_nt_kernel<TL, Epi>;
+                        int64_t block_stride_a = 0, int64_t block_stride_b = 0, int k_valid = 0) {
+  // ATN: A is [K][lda] with the M index along its rows (see gemm_mainloop); K blocking applies to B only
+  auto kern = gemm_nt_kernel<TL, Epi, ATN>;
+  constexpr int lds_bytes = ATN ? 2 * (kAtnStageBytes + TL::B_BYTES) : TL::LDS_BYTES;
   // the kernel addresses the rows of a tile with 32-bit byte offsets from the tile's first row
   const int64_t esz = (int64_t)sizeof(typename TL::T);
-  if ((TL::BM - 1) * lda * esz + 128 > (int64_t)UINT32_MAX || (TL::BN - 1) * ldb * esz + 128 > (int64_t)UINT32_MAX)
+  if ((ATN ? 127 : TL::BM - 1) * lda * esz + 512 > (int64_t)UINT32_MAX || (TL::BN - 1) * ldb * esz + 128 > (int64_t)UINT32_MAX)
     return false;
-  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), TL::LDS_BYTES)) return false;
+  if (ATN && (k_valid < 1 || k_valid > K)) return false;
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes)) return false;
   GemmShape g;
   g.A = A; g.B = B; g.lda = lda; g.ldb = ldb;
   g.batch_stride_a = bsa; g.batch_stride_b = bsb;
@@ -119,7 +122,8 @@ static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const vo
   g.slabs_per_block = k_block > 0 ? (int)(k_block / TL::BK) : (g.slabs_total > 0 ? g.slabs_total : 1);
   g.block_bytes_a = block_stride_a * (int64_t)sizeof(typename TL::T);
   g.block_bytes_b = block_stride_b * (int64_t)sizeof(typename TL::T);
-  hipLaunchKernelGGL(kern, dim3(g.grid_padded, batch), dim3(TL::NT), TL::LDS_BYTES, stream, g, epi);
+  g.k_valid = k_valid;
+  hipLaunchKernelGGL(kern, dim3(g.grid_padded, batch), dim3(TL::NT), lds_bytes, stream, g, epi);
   return launch_ok();
 }
 
@@ -207,7 +211,7 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   p.o_coef = c.take((size_t)batch * n * 16);
   p.o_losspart = c.take((size_t)batch * p.loss_blocks * 8 * (pooled ? 4 : 1));
   p.o_gstat = c.take(pooled ? (size_t)batch * 4 * 8 : 0);
-  p.o_xt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
+  p.o_xt = c.take(big_tiles ? 0 : (size_t)batch * d * p.nblk * p.tb * p.esz);  // big tiles read X as it is
   p.o_gt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
   p.o_splitk = c.take(p.split_k > 1 ? (size_t)p.split_k * batch * d * d * 4 : 0);
   p.total = c.off;
@@ -380,8 +384,10 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   if (!dR) return KT_OK;
   }
 
-  // token-minor copy of X for the last GEMM (zero padded to ldt tokens)
-  {
+  // bf16, d % 256 == 0: the last GEMM reads X as it is (transposing LDS reads); otherwise it needs a
+  // token-minor copy of X (zero padded to ldt tokens)
+  constexpr bool kXDirect = std::is_same<TDD, TB_BIG>::value;
+  if (!kXDirect) {
     ProfScope prof(3, st);
     if (sizeof(T) == 2) {
       dim3 grid((unsigned)ceil_div(p.ldt, 128), (unsigned)(d / 64), (unsigned)batch);
@@ -414,9 +420,14 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
     } else {
       e.C = dR; e.batch_stride = d * d; e.split_stride = 0;
     }
-    if (!launch_gemm<TDD>(XT, p.tb, d * p.nblk * p.tb, (int)d, GT, p.tb, d * p.nblk * p.tb, (int)d, p.ldt,
-                          p.slabs_per_split, (int)batch, e, st, p.tb, d * p.tb, d * p.tb))
-      return fail(KT_ERR_DEVICE, "gradient GEMM launch failed");
+    bool ok;
+    if constexpr (kXDirect)
+      ok = launch_gemm<TDD, EpiStore<TDD>, true>(Xp, ldx, n * ldx, (int)d, GT, p.tb, d * p.nblk * p.tb, (int)d, p.ldt,
+                                                 p.slabs_per_split, (int)batch, e, st, p.tb, 0, d * p.tb, (int)n);
+    else
+      ok = launch_gemm<TDD>(XT, p.tb, d * p.nblk * p.tb, (int)d, GT, p.tb, d * p.nblk * p.tb, (int)d, p.ldt,
+                            p.slabs_per_split, (int)batch, e, st, p.tb, d * p.tb, d * p.tb);
+    if (!ok) return fail(KT_ERR_DEVICE, "gradient GEMM launch failed");
     if (p.split_k > 1) {
       const int64_t count = batch * d * d;
       hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(ceil_div(count, 256) < 4096 ? ceil_div(count, 256) : 4096)),

@@ -37,23 +37,8 @@ constexpr int kF128BufBytes = kF128Tile * 256;  // one X or G tile: 128 rows of 
 constexpr int kF128GOff = 3 * kF128BufBytes;     // LDS: X[3] | G[2]
 constexpr int kF128LdsBytes = 5 * kF128BufBytes;  // 160 KiB
 
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-
 __device__ __forceinline__ int f128_xkey(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 __device__ __forceinline__ int f128_gkey(int t) { return ((t & 3) << 3) | ((t >> 2) & 7); }
-
-// Two transposing 8-byte LDS reads -> one MFMA operand (8 bf16 along K for this lane's row).
-// In a group of 16 lanes, lane r supplies the address of 4 consecutive features of token
-// t0 + r/4 starting at feature f0 + 4*(r%4); lane L of the group receives feature f0 + L of
-// tokens t0..t0+3.  `addr_lo` / `addr_hi` are this lane's addresses for tokens +0..3 / +4..7.
-__device__ __forceinline__ intx4 read_tr_operand(const char* lds, int addr_lo, int addr_hi) {
-  typedef __attribute__((address_space(3))) shortx4* lds_ptr;
-  const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds + addr_lo));
-  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds + addr_hi));
-  typedef short shortx8 __attribute__((ext_vector_type(8)));
-  const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(intx4, v);
-}
 
 // The matrix-core instructions of this kernel are written as inline assembly so that the
 // register file of every operand is fixed: R^T fragments and the dR accumulators live in

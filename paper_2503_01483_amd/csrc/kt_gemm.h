@@ -85,6 +85,21 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
   return row * kRowBytes + ((chunk ^ swizzle_key(row)) << 4);
 }
 
+// Two transposing 8-byte LDS reads (ds_read_b64_tr_b16) -> one MFMA operand: 8 values along K for
+// this lane's row, taken from a tile that is stored with K as the ROW index.  In a group of 16
+// lanes, lane r supplies the address of 4 consecutive columns of tile row k0 + r/4 starting at
+// column c0 + 4*(r%4); lane L of the group receives column c0 + L of rows k0..k0+3.
+// `addr_lo` / `addr_hi` are this lane's addresses for rows +0..3 / +4..7.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ intx4 read_tr_operand(const char* lds, int addr_lo, int addr_hi) {
+  typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+  const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds + addr_lo));
+  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds + addr_hi));
+  typedef short shortx8 __attribute__((ext_vector_type(8)));
+  const shortx8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(intx4, v);
+}
+
 // Geometry of one accumulator element, shared by every epilogue.
 template <class TL>
 struct Frag {
@@ -150,22 +165,36 @@ __device__ __forceinline__ void lds_barrier() {
 // the MFMAs that use them, each global load a whole slab before its LDS store, and
 // neither the LDS nor the vector-memory path ever sees a burst (a burst of 16 stores
 // per wave made the matrix pipe wait ~1000 cycles per slab).
-template <class TL>
+//
+// ATN (bf16, BM = 256): operand A is given with K as its ROW index instead, A[k][lda] with the tile's
+// 256 rows m as consecutive columns (the activations X [token][feature] for dR = X^T G: no
+// token-minor copy of X is needed).  K is walked in the order the other operand stores it
+// (token_position() of the epilogues: position 4a + b of a 128-token group is token a + 32 b).
+// A slab is then 64 tile rows of 512 bytes, padded to 576 so that the four consecutive rows a
+// transposing read touches lie 64 bytes apart in the bank window; fragments come from
+// read_tr_operand.  Rows k >= k_valid are not read (the last valid row is read instead; the other
+// operand is zero there).
+constexpr int kAtnRowBytes = 576;
+constexpr int kAtnStageBytes = 64 * kAtnRowBytes;
+
+template <class TL, bool ATN = false>
 __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__ A, int64_t lda,
                                               int M, int m0,
                                               const typename TL::T* __restrict__ B, int64_t ldb,
                                               int N, int n0, int slab0, int k_slabs,
                                               int slabs_per_block, int64_t block_bytes_a,
                                               int64_t block_bytes_b,
-                                              floatx16 (&acc)[TL::MB][TL::NB], char* lds) {
+                                              floatx16 (&acc)[TL::MB][TL::NB], char* lds, int k_valid = 0) {
   using T = typename TL::T;
+  static_assert(!ATN || (sizeof(T) == 2 && TL::BM == 256 && TL::NT == 256), "ATN: bf16, 256 tile rows, 4 waves");
+  constexpr int A_STAGE = ATN ? kAtnStageBytes : TL::A_BYTES;
   constexpr int EPC = 16 / (int)sizeof(T);  // elements per 16-byte chunk
   constexpr int MB = TL::MB, NB = TL::NB, NMMA = MB * NB, NFRAG = MB + NB;
   constexpr int A_LD = TL::A_LD, B_LD = TL::B_LD, NLD = A_LD + B_LD;
   constexpr int ROWS_PER_PASS = TL::NT / kChunks;
   // LDS layout: [A stage 0][A stage 1][B stage 0][B stage 1]; every stage offset and
   // every per-block row offset below is a compile-time immediate of the ds_ instruction.
-  constexpr int B_BASE = 2 * TL::A_BYTES;
+  constexpr int B_BASE = 2 * A_STAGE;
   static_assert(kChunks / 2 == 4, "the schedule is written for 4 K sub-steps per slab");
   static_assert(ROWS_PER_PASS % 16 == 0, "swizzle key must not change between load passes");
   static_assert(NFRAG <= NMMA && NLD <= 3 * NMMA, "not enough MFMA slots to hide the memory instructions");
@@ -175,23 +204,49 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   const int lchunk = tid & 7;
 
   // global addressing: uniform 64-bit base (advanced per slab) + 32-bit byte offsets
-  const char* Ab = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+  const char* Ab = reinterpret_cast<const char*>(ATN ? A + m0 : A + (int64_t)m0 * lda);
   const char* Bb = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
   // byte offsets of K slab `slab` (relative to slab0) inside a row of A / of B: uniform values
   int64_t ka = 0, kb = 0;
+  uint32_t og[NLD];
+  // ATN: thread (chunk tid & 31 of the 512-byte row, row group tid >> 5) moves tile rows
+  // (tid >> 5) + 8 i of a slab; tile row pr of slab g holds position 64 (g & 1) + pr of 128-token
+  // group g >> 1, i.e. token (pr >> 2) + 16 (g & 1) + 32 (pr & 3) of the group.
+  const int atn_chunk = tid & 31, atn_rg = tid >> 5;
+  auto atn_token = [&](int i) __attribute__((always_inline)) {
+    const int pr = atn_rg + 8 * i;
+    return (pr >> 2) + 32 * (pr & 3);
+  };
   auto locate = [&](int slab) __attribute__((always_inline)) {
     const int g = slab0 + slab;
     const int blk = g / slabs_per_block;
     const int64_t in_blk = (int64_t)(g - blk * slabs_per_block) * kRowBytes;
-    ka = blk * block_bytes_a + in_blk;
     kb = blk * block_bytes_b + in_blk;
+    if constexpr (ATN) {
+      const int grp0 = (g >> 1) * 128, half16 = (g & 1) * 16;  // tile row 0 of this slab is token grp0 + half16
+      ka = (int64_t)(grp0 + half16) * lda * (int64_t)sizeof(T);
+      if (grp0 + 128 > k_valid) {  // last, partial group: rows past the end read the last valid token
+        ka = (int64_t)grp0 * lda * (int64_t)sizeof(T);
+        const int last = k_valid - 1 - grp0;  // >= 0: the group starts inside the operand
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) {
+          const int t = half16 + atn_token(i);
+          og[i] = (uint32_t)(((int64_t)(t < last ? t : last) * lda + atn_chunk * EPC) * (int64_t)sizeof(T));
+        }
+      }
+    } else {
+      ka = blk * block_bytes_a + in_blk;
+    }
   };
-  uint32_t og[NLD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
-    int row = lrow + i * ROWS_PER_PASS;
-    row = (m0 + row < M) ? row : (M - 1 - m0);
-    og[i] = (uint32_t)(((int64_t)row * lda + lchunk * EPC) * (int64_t)sizeof(T));
+    if constexpr (ATN) {
+      og[i] = (uint32_t)(((int64_t)atn_token(i) * lda + atn_chunk * EPC) * (int64_t)sizeof(T));
+    } else {
+      int row = lrow + i * ROWS_PER_PASS;
+      row = (m0 + row < M) ? row : (M - 1 - m0);
+      og[i] = (uint32_t)(((int64_t)row * lda + lchunk * EPC) * (int64_t)sizeof(T));
+    }
   }
 #pragma unroll
   for (int i = 0; i < B_LD; ++i) {
@@ -200,6 +255,7 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
     og[A_LD + i] = (uint32_t)(((int64_t)row * ldb + lchunk * EPC) * (int64_t)sizeof(T));
   }
   const int st_off = lds_off(lrow, lchunk);  // + i*ROWS_PER_PASS*128 per pass (same key)
+  const int st_off_atn = atn_rg * kAtnRowBytes + atn_chunk * 16;  // + i * 8 rows per load
 
   const Frag<TL> f;
   // fragment addresses: one per K sub-step and operand; blocks and stages are immediates
@@ -211,6 +267,10 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
     fa_s[s] = (f.wm * TL::WTM + (f.lane & 31)) * kRowBytes + coff;
     fb_s[s] = B_BASE + (f.wn * TL::WTN + (f.lane & 31)) * kRowBytes + coff;
   }
+  // ATN fragments: tile rows 16 s + tr_row (+4), columns (features) wm * WTM + 32 block + tr_col ..
+  const int atn_g16 = f.lane >> 4, atn_rr = f.lane & 15;
+  const int atn_tr = (8 * (atn_g16 >> 1) + (atn_rr >> 2)) * kAtnRowBytes +
+                     (f.wm * TL::WTM + 16 * (atn_g16 & 1) + 4 * (atn_rr & 3)) * 2;
 
   intx4 rg[NLD];        // one K slab in flight from global memory
   intx4 fr[2][NFRAG];   // MFMA fragments, double buffered: [buf][0..MB) = A, [MB..) = B
@@ -224,15 +284,22 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   auto lstore = [&](auto i_c, auto stage_c) __attribute__((always_inline)) {
     constexpr int i = decltype(i_c)::value;
     constexpr int stage = decltype(stage_c)::value;
-    constexpr int off = i < A_LD ? stage * TL::A_BYTES + i * ROWS_PER_PASS * kRowBytes
-                                 : B_BASE + stage * TL::B_BYTES + (i - A_LD) * ROWS_PER_PASS * kRowBytes;
-    *reinterpret_cast<intx4*>(lds + st_off + off) = rg[i];
+    if constexpr (ATN && i < A_LD) {
+      *reinterpret_cast<intx4*>(lds + st_off_atn + stage * A_STAGE + i * 8 * kAtnRowBytes) = rg[i];
+    } else {
+      constexpr int off = i < A_LD ? stage * A_STAGE + i * ROWS_PER_PASS * kRowBytes
+                                   : B_BASE + stage * TL::B_BYTES + (i - A_LD) * ROWS_PER_PASS * kRowBytes;
+      *reinterpret_cast<intx4*>(lds + st_off + off) = rg[i];
+    }
   };
   auto fread = [&](auto buf_c, auto i_c, auto stage_c, auto s_c) __attribute__((always_inline)) {
     constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value;
     constexpr int stage = decltype(stage_c)::value, s = decltype(s_c)::value;
-    if constexpr (i < MB)
-      fr[buf][i] = *reinterpret_cast<const intx4*>(lds + fa_s[s] + stage * TL::A_BYTES + i * 32 * kRowBytes);
+    if constexpr (ATN && i < MB) {
+      constexpr int off = stage * A_STAGE + s * 16 * kAtnRowBytes + i * 64;
+      fr[buf][i] = read_tr_operand(lds, atn_tr + off, atn_tr + off + 4 * kAtnRowBytes);
+    } else if constexpr (i < MB)
+      fr[buf][i] = *reinterpret_cast<const intx4*>(lds + fa_s[s] + stage * A_STAGE + i * 32 * kRowBytes);
     else
       fr[buf][i] = *reinterpret_cast<const intx4*>(lds + fb_s[s] + stage * TL::B_BYTES + (i - MB) * 32 * kRowBytes);
   };
@@ -315,6 +382,7 @@ struct GemmShape {
   int grid_padded;   // tiles_total rounded up to a multiple of 8
   int slabs_per_block;             // K blocking of the operand rows (see gemm_mainloop)
   int64_t block_bytes_a, block_bytes_b;
+  int k_valid;                     // ATN: rows of A that exist (K may be padded beyond them)
 };
 
 // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them,
@@ -340,7 +408,7 @@ __device__ __forceinline__ bool tile_of_block(const GemmShape& g, int& tm, int& 
   return true;
 }
 
-template <class TL, class Epi>
+template <class TL, class Epi, bool ATN = false>
 __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmShape g, Epi epi) {
   extern __shared__ __align__(16) char lds[];
   using T = typename TL::T;
@@ -363,8 +431,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmShape g, Epi epi) {
 
   const T* A = static_cast<const T*>(g.A) + (int64_t)batch * g.batch_stride_a;
   const T* B = static_cast<const T*>(g.B) + (int64_t)batch * g.batch_stride_b;
-  gemm_mainloop<TL>(A, g.lda, g.M, m0, B, g.ldb, g.N, n0, slab0, slabs, g.slabs_per_block,
-                    g.block_bytes_a, g.block_bytes_b, acc, lds);
+  gemm_mainloop<TL, ATN>(A, g.lda, g.M, m0, B, g.ldb, g.N, n0, slab0, slabs, g.slabs_per_block,
+                         g.block_bytes_a, g.block_bytes_b, acc, lds, g.k_valid);
   epi(acc, batch, tm, tn, ks, m0, n0);
 }
 

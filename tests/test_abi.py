@@ -35,7 +35,7 @@ def test_workspace_bytes():
     f = kt.kt_workspace_bytes
     assert f(kt.KT_OP_LOSS_GRAD, 1, 2048, 256, kt.KT_F32) > 2 * 2048 * 256 * 4
     big = f(kt.KT_OP_LOSS_GRAD, 1, 131072, 4096, kt.KT_BF16)
-    assert 2 * 2**30 < big < 3 * 2**30          # token-minor X and G copies dominate
+    assert 2**30 < big < 1.25 * 2**30           # the token-minor dL/dY dominates (X is read in place)
     assert f(kt.KT_OP_LOSS_GRAD, 1, 100, 100, kt.KT_BF16) == 0   # d not a multiple of 128
     assert f(kt.KT_OP_LOSS_GRAD, 0, 100, 128, kt.KT_BF16) == 0
     assert f(kt.KT_OP_CAYLEY, 1, 0, 4096, kt.KT_F32) >= 5 * 4096 * 4096 * 4
