@@ -36,7 +36,10 @@ def test_fp32_ragged_shapes(n, d):
 
 @pytest.mark.parametrize("n,d,batch", [(1, 128, 1), (200, 128, 3), (777, 256, 1), (1000, 384, 2),
                                         (520, 512, 1), (2048, 768, 1), (300, 1024, 1),
-                                        (9000, 256, 1), (4200, 128, 2)])  # several token blocks
+                                        (9000, 256, 1), (4200, 128, 2),   # several token blocks
+                                        # d % 256 == 0: the gradient GEMM reads X in place; partial last
+                                        # 128-token groups (one token, half a group, two tokens past one), batches
+                                        (1, 256, 1), (64, 256, 1), (130, 512, 2), (600, 256, 3), (257, 1024, 1)])
 def test_bf16_shapes(n, d, batch):
     xs = [ktgen.make_x(n, d, seed=7 * b + n, outlier_cols=4, outlier_scale=60.0, t_frac=0.05,
                        dtype="bf16") for b in range(batch)]
