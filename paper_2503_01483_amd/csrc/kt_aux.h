@@ -127,6 +127,28 @@ __device__ __forceinline__ double block_sum_256(double v, double* sh) {
   return sh[0];
 }
 
+// Moments of one token row from the P partials the forward epilogue wrote ({mean_p, sum c^2, sum c^3,
+// sum c^4} about the partial's own mean, d / P features each), merged in fp64 with the shift
+// formulas  sum (c + e)^k = sum c^k + k e sum c^(k-1) + ...  (sum c = 0 inside a partial):
+// mu = row mean, M[0..2] = sums of (y - mu)^2, ^3, ^4 over the row.
+__device__ __forceinline__ void row_central_sums(const floatx4* __restrict__ part, int P, int n, int64_t batch,
+                                                 int token, int d, double& mu, double (&M)[3]) {
+  const double cnt = (double)d / (double)P;
+  double m = 0.0;
+  for (int p = 0; p < P; ++p) m += (double)part[((int64_t)batch * P + p) * n + token][0];
+  mu = m / (double)P;
+  double M2 = 0.0, M3 = 0.0, M4 = 0.0;
+  for (int p = 0; p < P; ++p) {
+    const floatx4 v = part[((int64_t)batch * P + p) * n + token];
+    const double e = (double)v[0] - mu, e2 = e * e;
+    M2 += (double)v[1] + cnt * e2;
+    M3 += (double)v[2] + 3.0 * e * (double)v[1] + cnt * e2 * e;
+    M4 += (double)v[3] + 4.0 * e * (double)v[2] + 6.0 * e2 * (double)v[1] + cnt * e2 * e2;
+  }
+  M[0] = M2; M[1] = M3; M[2] = M4;
+}
+
+
 // Per token: add the P partial raw sums in fixed order (fp64), turn them into the
 // central moments of Eq. 3, kappa, the loss term and the coefficients the backward
 // epilogue needs.  One thread per token; grid = (ceil(n/256), batch).
@@ -140,17 +162,12 @@ __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __res
   const int token = blockIdx.x * 256 + threadIdx.x;
   double term = 0.0;
   if (token < n) {
-    double S1 = 0, S2 = 0, S3 = 0, S4 = 0;
-    for (int p = 0; p < P; ++p) {
-      const floatx4 v = part[((int64_t)batch * P + p) * n + token];
-      S1 += v[0]; S2 += v[1]; S3 += v[2]; S4 += v[3];
-    }
+    double mu, M[3];
+    row_central_sums(part, P, n, batch, token, d, mu, M);
     const double inv_d = 1.0 / (double)d;
-    const double mu = S1 * inv_d, r2 = S2 * inv_d, r3 = S3 * inv_d, r4 = S4 * inv_d;
-    const double m2 = r2 - mu * mu;
-    const double m3 = r3 - 3.0 * mu * r2 + 2.0 * mu * mu * mu;
-    const double m4 = r4 - 4.0 * mu * r3 + 6.0 * mu * mu * r2 - 3.0 * mu * mu * mu * mu;
-    const bool ok = m2 > 1e-5 * r2;  // fp32 sums cannot resolve less spread than this
+    const double m2 = M[0] * inv_d, m3 = M[1] * inv_d, m4 = M[2] * inv_d;
+    const double r2 = m2 + mu * mu;
+    const bool ok = m2 > 1e-5 * r2;  // a row this flat counts as having no spread (same rule as the d = 128 kernel)
     double kappa = 0.0, alpha = 0.0, beta = 0.0;
     if (ok) {
       kappa = m4 / (m2 * m2);
@@ -176,17 +193,18 @@ __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __res
 }
 
 // ---- pooled (paper-literal) loss: kurtosis of ALL entries of RMSNorm(X R) as one sample ------
-// Row sums of z^k = (y / rho)^k follow from the row's raw sums of y^k, so the forward GEMM with the
+// Row sums of z^k = (y / rho)^k follow from the row's sums of y^k, so the forward GEMM with the
 // moment epilogue is used unchanged.  Stage 1: per token rho and the block partials of the four
 // pooled raw sums.  grid = (ceil(n/256), batch).
 __device__ __forceinline__ void pooled_row_sums(const floatx4* __restrict__ part, int P, int n, int64_t batch,
                                                 int token, int d, double rms_eps, double& inv_rho,
                                                 double (&Z)[4]) {
-  double S1 = 0, S2 = 0, S3 = 0, S4 = 0;
-  for (int p = 0; p < P; ++p) {
-    const floatx4 v = part[((int64_t)batch * P + p) * n + token];
-    S1 += v[0]; S2 += v[1]; S3 += v[2]; S4 += v[3];
-  }
+  double mu, M[3];
+  row_central_sums(part, P, n, batch, token, d, mu, M);
+  // raw sums of y^k over the row, from the central ones (fp64: nothing is lost going back)
+  const double dd = (double)d, mu2 = mu * mu;
+  const double S1 = dd * mu, S2 = M[0] + dd * mu2, S3 = M[1] + 3.0 * mu * M[0] + dd * mu2 * mu,
+               S4 = M[2] + 4.0 * mu * M[1] + 6.0 * mu2 * M[0] + dd * mu2 * mu2;
   const double rho2 = S2 / (double)d + rms_eps;
   inv_rho = rho2 > 0.0 ? 1.0 / sqrt(rho2) : 0.0;  // a row of zeros: z = 0
   const double i2 = inv_rho * inv_rho;

@@ -19,10 +19,12 @@ struct EpiBase {
   __device__ __forceinline__ bool skip(int) const { return false; }
 };
 
-// ---- forward pass: per-token raw moments of y over the hidden dimension ----------
+// ---- forward pass: per-token moments of y over the hidden dimension ---------------
 // m = output feature (reduced in registers), n = token (one per lane).
-// part[(batch*P + p)*n_tokens + token] = {sum y, sum y^2, sum y^3, sum y^4} over the
-// WTM features wave-row p = tm*WGM + wm owns.
+// part[(batch*P + p)*n_tokens + token] = {mean_p, sum c^2, sum c^3, sum c^4}, c = y - mean_p, over
+// the WTM features wave-row p = tm*WGM + wm owns: the mean first, then sums about it (two passes
+// over the registers), so that a row whose mean is large against its spread loses nothing to
+// cancellation in fp32; the partials of a row are merged in fp64 (row_central_sums in kt_aux.h).
 template <class TL>
 struct EpiMoments : EpiBase {
   floatx4* part;
@@ -31,30 +33,42 @@ struct EpiMoments : EpiBase {
                                              int, int, int m0, int n0) const {
     const Frag<TL> f;
     const int p = tm * TL::WGM + f.wm;
+    int blocks = 0;
+#pragma unroll
+    for (int mb = 0; mb < TL::MB; ++mb) blocks += (m0 + f.m_block(mb) < d) ? 1 : 0;
+    const float inv_cnt = blocks > 0 ? 1.0f / (float)(32 * blocks) : 0.f;
 #pragma unroll
     for (int nb = 0; nb < TL::NB; ++nb) {
-      float s1 = 0.f, s2 = 0.f, s3 = 0.f, s4 = 0.f;
+      float s1 = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < TL::MB; ++mb) {
+        if (m0 + f.m_block(mb) < d) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s1 += acc[mb][nb][r];
+        }
+      }
+      s1 += __shfl_xor(s1, 32);
+      const float mean = s1 * inv_cnt;
+      float s2 = 0.f, s3 = 0.f, s4 = 0.f;
 #pragma unroll
       for (int mb = 0; mb < TL::MB; ++mb) {
         if (m0 + f.m_block(mb) < d) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float y = acc[mb][nb][r];
-            const float y2 = y * y;
-            s1 += y;
-            s2 += y2;
-            s3 = fmaf(y2, y, s3);
-            s4 = fmaf(y2, y2, s4);
+            const float c = acc[mb][nb][r] - mean;
+            const float c2 = c * c;
+            s2 += c2;
+            s3 = fmaf(c2, c, s3);
+            s4 = fmaf(c2, c2, s4);
           }
         }
       }
-      s1 += __shfl_xor(s1, 32);
       s2 += __shfl_xor(s2, 32);
       s3 += __shfl_xor(s3, 32);
       s4 += __shfl_xor(s4, 32);
       const int token = n0 + f.n_of(nb);
       if (f.half == 0 && token < n_tokens) {
-        floatx4 v = {s1, s2, s3, s4};
+        floatx4 v = {mean, s2, s3, s4};
         part[((int64_t)batch * P + p) * n_tokens + token] = v;
       }
     }

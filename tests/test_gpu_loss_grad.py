@@ -142,6 +142,31 @@ def test_c2_shape_chunk_vs_oracle_and_additivity():
     assert abs(2560 * full["loss"][0] - lacc) <= 1e-5 * lacc
 
 
+@pytest.mark.parametrize("dtype,d,tol", [("f32", 512, TOL_F32), ("bf16", 512, TOL_BF16), ("bf16", 128, TOL_BF16)])
+def test_rows_with_a_mean_far_above_their_spread(dtype, d, tol):
+    """Kurtosis is shift invariant, but sums of raw powers are not robust to a shift: rows are moved along
+    R 1 so that every rotated value gains the same offset (mean / sigma = 10, 30, 100).  The path keeps
+    central sums per 128 features, so the tolerances of the benchmark definition hold throughout; feeding
+    the centred rotation R (I - 11^T/d) instead must give the same row values."""
+    n = 600
+    R = ktgen.random_orthogonal(d, seed=1)
+    Rd = R.double()
+    shift_dir = Rd @ torch.ones(d, dtype=torch.float64)       # x + c (R 1)^T  ->  y + c 1^T
+    Z = torch.randn(n, d, generator=torch.Generator().manual_seed(2), dtype=torch.float64)
+    Rc = (Rd - Rd.mean(1, keepdim=True)).float()
+    for c in (10.0, 30.0, 100.0):
+        X = (Z + c * shift_dir).to(torch.float32 if dtype == "f32" else torch.bfloat16)
+        g = gpu_loss_grad(X, R)
+        o = oracle_loss_grad(X, R)
+        assert abs(float(np.mean(o["row_kurt"])) - 3.0) < 0.3            # the oracle sees ordinary Gaussian rows
+        check_loss_grad(g, o, tol)
+        gc = gpu_loss_grad(X, Rc)
+        oc = oracle_loss_grad(X, Rc)
+        check_loss_grad(gc, oc, tol)
+        if dtype == "f32":
+            assert np.allclose(gc["row_kurt"], g["row_kurt"], rtol=2e-4)
+
+
 # ---- head-dimension problems (d = 128, bf16) take the single-pass fused kernel -------------------
 @pytest.mark.parametrize("n,batch,kt_", [(255, 1, 0.0), (256, 2, 0.0), (257, 1, 0.0), (3000, 5, 0.0),
                                           (20000, 1, 0.0), (1500, 2, 2.6),
