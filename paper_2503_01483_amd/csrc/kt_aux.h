@@ -148,10 +148,8 @@ __device__ __forceinline__ void row_central_sums(const floatx4* __restrict__ par
   M[0] = M2; M[1] = M3; M[2] = M4;
 }
 
-
-// Per token: add the P partial raw sums in fixed order (fp64), turn them into the
-// central moments of Eq. 3, kappa, the loss term and the coefficients the backward
-// epilogue needs.  One thread per token; grid = (ceil(n/256), batch).
+// Per token: merge the P partials in fixed order (fp64) into the central moments of
+// Eq. 3, then kappa, the loss term and the coefficients the backward epilogue needs.  One thread per token; grid = (ceil(n/256), batch).
 __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __restrict__ part, int P,
                                                             int n, int d, float kappa_target,
                                                             floatx4* __restrict__ coef,
