@@ -86,7 +86,7 @@ constexpr int kNumCUs = 256;
 // feature row is contiguous, blocks follow each other feature-row-set by feature-row-set, so
 // the 256 rows a tile streams together span 2 MiB per block instead of one page per row.
 constexpr int64_t kTokenBlock = 4096;
-constexpr int kHadMfmaFrom = 44;  // bf16 Hadamard factors of at least this order run on the matrix cores (measured: the vector kernel wins below)
+constexpr int kHadMfmaFrom = 12;  // bf16 Hadamard factors of at least this order run on the matrix cores (measured: the vector kernel wins for 4 and 8)
 constexpr int kSensBlocks = 1024;  // workgroups of the sensitivity sweeps
 constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
@@ -749,7 +749,7 @@ static kt_status run_hadamard(const void* X, int64_t ldx, void* Y, int64_t ldy, 
     const int MB = (m + 31) / 32, KS = (m + 15) / 16;
     int lognb = 0;  // blocks of 32 columns per wave: as many as keep m * NBW <= 128, fit the segment and 64 KiB of LDS
     while ((2 << lognb) * m <= 128 && (256 << lognb) <= p2 && 2 * 16 * KS * (512 << lognb) <= 65536) ++lognb;
-    const size_t lds = (size_t)32 * MB * 32 * KS + 2 * (size_t)16 * KS * (256 << lognb);
+    const size_t lds = (size_t)32 * MB * 32 * KS + (size_t)16 * KS * (256 << lognb) + (size_t)32 * MB * ((256 << lognb) + 16);
     if (!ensure_dynamic_lds(reinterpret_cast<const void*>(hadamard_cross_mfma_kernel), lds))
       return fail(KT_ERR_DEVICE, "the Hadamard factor kernel needs %zu bytes of LDS per workgroup", lds);
     const int64_t tiles_m = n * (p2 / (128 << lognb));

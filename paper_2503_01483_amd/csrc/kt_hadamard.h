@@ -275,14 +275,16 @@ __global__ __launch_bounds__(256) void hadamard_cross_kernel(T* __restrict__ Y, 
 // The same factor for bf16 rows on the matrix cores: entries +-1 and bf16 inputs make every product
 // exact, the sums run in fp32 as in the vector version.  Per tile of 128 NBW columns of one row
 // (NBW = 2^lognb blocks of 32 columns per wave, chosen so that a tile holds about 128 x 128 values):
-//   Y_tile[a][c] = sum_a' H_m[a'][a] x[a'][c]   =   A (M = a, K = a') times B (K = a', N = c)
-// A = H_m^T sits in LDS as bf16, K-minor, zero-padded to 32-row blocks and 16-wide K steps, and is
-// read as ordinary 16-byte fragments.  The x tile sits in LDS as loaded (row a' = the tile's columns);
-// its fragments (8 consecutive a' of one column per lane) come from the transposing read
-// ds_read_b64_tr_b16.  Rows a' >= m of the tile are zero and never written.  Results go through
-// LDS once more so that the stores are whole row pieces; the loads of the next tile are in flight
-// while a tile is worked on.  m NBW <= 128.
-// LDS bytes: 32 MB * 32 KS (A) + 2 * 16 KS * 256 NBW (x tile, y tile), MB = ceil(m/32), KS = ceil(m/16).
+//   Y_tile^T[c][a] = sum_a' x[a'][c] H_m[a'][a]   =   A (M = c, K = a') times B (K = a', N = a)
+// H_m^T sits in LDS as bf16, K-minor, zero-padded to 32-row blocks and 16-wide K steps, and is
+// read as ordinary 16-byte fragments (the B operand).  The x tile sits in LDS as loaded (row a' =
+// the tile's columns); its fragments (8 consecutive a' of one column per lane, the A operand) come
+// from the transposing read ds_read_b64_tr_b16.  Rows a' >= m of the tile are zero and never
+// written.  In the accumulators a lane then owns ONE output a and 4 x 4 consecutive columns, so the
+// results go to the y tile in LDS with 8-byte stores (rows padded by 16 bytes against bank
+// conflicts) and from there to memory as whole row pieces; the loads of the next tile are in
+// flight while a tile is worked on.  m NBW <= 128.
+// LDS bytes: 32 MB * 32 KS (H) + 16 KS * 256 NBW (x tile) + 32 MB * (256 NBW + 16) (y tile).
 __global__ __launch_bounds__(256) void hadamard_cross_mfma_kernel(__bf16* __restrict__ Y, int64_t ldy, int64_t n,
                                                                   int m, int p2, int kind, int lognb) {
   extern __shared__ __align__(16) char cross_raw[];
@@ -292,6 +294,7 @@ __global__ __launch_bounds__(256) void hadamard_cross_mfma_kernel(__bf16* __rest
   char* A = cross_raw;
   char* xt = A + 32 * MB * a_stride;
   char* yt = xt + 16 * KS * rowb;
+  const int rowy = rowb + 16;  // bytes per row of the y tile
   unsigned char* isq = reinterpret_cast<unsigned char*>(yt);  // scratch during set-up only
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, l32 = lane & 31;
@@ -381,17 +384,23 @@ __global__ __launch_bounds__(256) void hadamard_cross_mfma_kernel(__bf16* __rest
         for (int mb = 0; mb < 4; ++mb)
           if (mb < MB) {
             const intx4 af = *reinterpret_cast<const intx4*>(A + (32 * mb + l32) * a_stride + (2 * s + half) * 16);
-            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af),
-                                                              __builtin_bit_cast(bf16x8, bf), acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bf),
+                                                              __builtin_bit_cast(bf16x8, af), acc[mb], 0, 0, 0);
           }
       }
+      // lane: output a = 32 mb + l32, columns col0 + 8 (r / 4) + 4 half + (r & 3)
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
         if (mb < MB) {
+          const int a = 32 * mb + l32;
+          if (a < m) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int a = 32 * mb + ((r >> 2) << 3) + (half << 2) + (r & 3);
-            if (a < m) reinterpret_cast<__bf16*>(yt)[a * tcols + col0 + l32] = (__bf16)acc[mb][r];
+            for (int rg = 0; rg < 4; ++rg) {
+              typedef __bf16 bf16x4v __attribute__((ext_vector_type(4)));
+              const bf16x4v o = {(__bf16)acc[mb][4 * rg], (__bf16)acc[mb][4 * rg + 1], (__bf16)acc[mb][4 * rg + 2],
+                                 (__bf16)acc[mb][4 * rg + 3]};
+              *reinterpret_cast<bf16x4v*>(yt + a * rowy + (col0 + 8 * rg + 4 * half) * 2) = o;
+            }
           }
         }
     }
@@ -401,7 +410,7 @@ __global__ __launch_bounds__(256) void hadamard_cross_mfma_kernel(__bf16* __rest
       const int c = tid + 256 * i, a = c >> chunk_shift;
       if (a < m)
         *reinterpret_cast<intx4*>(base + (int64_t)a * p2 + (c & chunk_mask) * 8) =
-            *reinterpret_cast<const intx4*>(yt + a * rowb + (c & chunk_mask) * 16);
+            *reinterpret_cast<const intx4*>(yt + a * rowy + (c & chunk_mask) * 16);
     }
     // the next tile's stores to xt come after every wave has passed the barrier above (its reads of
     // xt are done), its stores to yt after the next barrier (the copy-out above is done)
