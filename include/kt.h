@@ -199,6 +199,11 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
  *  codes      [batch][n][d] int8, one code per byte in [-7, 7], or NULL.
  *  err        [batch][n][2] fp32 or NULL.
  *  A row with scale 0 gets codes 0.
+ *  Workspace: kt_workspace_bytes(KT_OP_FAKEQUANT, ...).  It holds an fp32 staging buffer of at most
+ *  256 MiB: when the scales are computed here, y is rotated once, a slice of token rows at a time,
+ *  and a row kernel takes the maximum and quantises the staged values (one GEMM pass instead of a
+ *  second one that recomputes y).  With scales_in the codes come straight out of the GEMM's registers.
+ *  d = 128 in bf16 is a single fused pass with no staging.
  */
 kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, int64_t ldr,
                                    int64_t batch, int64_t n, int64_t d,

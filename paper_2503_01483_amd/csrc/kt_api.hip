@@ -255,8 +255,13 @@ struct QuantPlan {
   bool fp32;
   size_t esz;
   int P, PN;
-  size_t o_rt, o_amax, o_scales, o_errpart, total;
+  // Scales computed here AND codes or errors wanted: Y goes through an fp32 staging buffer of at most
+  // kQuantStageBytes, `problems` whole problems or `rows` tokens of one problem per launch pair.
+  int64_t stage_problems, stage_rows;
+  size_t o_rt, o_amax, o_scales, o_errpart, o_y, total;
 };
+
+constexpr int64_t kQuantStageBytes = (int64_t)256 << 20;  // 64 MiB .. 4 GiB measured alike at d = 4096
 
 static QuantPlan plan_quant(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
   QuantPlan p;
@@ -277,6 +282,10 @@ static QuantPlan plan_quant(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
   p.o_amax = c.take((size_t)batch * p.P * n * 4);
   p.o_scales = c.take((size_t)batch * n * 4);
   p.o_errpart = c.take((size_t)batch * p.P * n * 8);
+  int64_t cap = kQuantStageBytes / (4 * d) / 256 * 256;  // >= 4096 token rows at d <= 16384
+  p.stage_rows = n < cap ? n : cap;
+  p.stage_problems = n <= cap ? (cap / n < batch ? cap / n : batch) : 1;
+  p.o_y = c.take((size_t)p.stage_problems * p.stage_rows * d * 4);
   p.total = c.off;
   return p;
 }
@@ -481,6 +490,37 @@ static kt_status run_quant(const QuantPlan& p, const void* X, int64_t ldx, const
   const T* Xp = static_cast<const T*>(X);
   if (!prep_rt<T>(R, ldr, rdt, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
   const float* scales = scales_in;
+  if (!scales_in && (codes || err)) {
+    // One GEMM instead of two: Y = X R is staged in fp32 (token-major: tokens on the rows of the GEMM), a
+    // row kernel takes the maximum and quantises.  4 n d bytes written and read against 2 n d^2 flop saved.
+    float* Ybuf = reinterpret_cast<float*>(ws + p.o_y);
+    for (int64_t b0 = 0; b0 < batch; b0 += p.stage_problems) {
+      const int64_t nb = batch - b0 < p.stage_problems ? batch - b0 : p.stage_problems;
+      for (int64_t t0 = 0; t0 < n; t0 += p.stage_rows) {
+        const int64_t nt = n - t0 < p.stage_rows ? n - t0 : p.stage_rows;
+        EpiStore<TQ> e;
+        e.C = Ybuf; e.ldc = d; e.batch_stride = nt * d; e.split_stride = 0; e.M = (int)nt; e.N = (int)d;
+        if (!launch_gemm<TQ>(Xp + (b0 * n + t0) * ldx, ldx, n * ldx, (int)nt, RT + b0 * d * d, d, d * d, (int)d, d,
+                             0, (int)nb, e, st))
+          return fail(KT_ERR_DEVICE, "rotation GEMM launch failed");
+        const int64_t rows = nb * nt, row0 = b0 * n + t0;
+        float* so = scales_out ? scales_out + row0 : nullptr;
+        int8_t* co = codes ? codes + row0 * d : nullptr;
+        float2* eo = err ? reinterpret_cast<float2*>(err) + row0 : nullptr;
+        const dim3 grid((unsigned)ceil_div(rows, 4));
+        if (d <= 1024)
+          hipLaunchKernelGGL((quant_rows_kernel<4, true>), grid, dim3(256), 0, st, Ybuf, rows, (int)d, clip, so, co, eo);
+        else if (d <= 4096)
+          hipLaunchKernelGGL((quant_rows_kernel<16, true>), grid, dim3(256), 0, st, Ybuf, rows, (int)d, clip, so, co, eo);
+        else if (d <= 8192)
+          hipLaunchKernelGGL((quant_rows_kernel<32, true>), grid, dim3(256), 0, st, Ybuf, rows, (int)d, clip, so, co, eo);
+        else
+          hipLaunchKernelGGL((quant_rows_kernel<1, false>), grid, dim3(256), 0, st, Ybuf, rows, (int)d, clip, so, co, eo);
+        if (!launch_ok()) return fail(KT_ERR_DEVICE, "row quantiser launch failed");
+      }
+    }
+    return KT_OK;
+  }
   if (!scales_in) {
     EpiAmax<TFWD> e;
     e.part = amax; e.n_tokens = (int)n; e.d = (int)d; e.P = p.P;

@@ -589,6 +589,80 @@ __global__ __launch_bounds__(256) void quant_err_kernel(const float2* __restrict
   err[batch * n + t] = make_float2(e, y);
 }
 
+// Fake-quant of token rows of a materialised fp32 Y ([rows][d], contiguous): one wave per row, no
+// workgroup barrier.  The row is read once (KEEP: it stays in CH float4 registers per lane, d <= 256 CH)
+// or twice (the second read comes out of the caches); amax, s = (clip amax)/7, one reciprocal per row,
+// q = clamp(rint(y * (1/s)), -7, 7), four codes per 4-byte store, {sum (y - q s)^2, sum y^2}.
+// scales_out / codes / err are indexed from the first row of this launch; any of them may be null.
+template <int CH, bool KEEP>
+__global__ __launch_bounds__(256) void quant_rows_kernel(const float* __restrict__ Y, int64_t rows, int d,
+                                                         float clip, float* __restrict__ scales_out,
+                                                         int8_t* __restrict__ codes, float2* __restrict__ err) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float4* y4 = reinterpret_cast<const float4*>(Y + row * d) + lane;
+  const int nch = (d + 255) >> 8;  // chunks of 256 values; d % 128 == 0: the last one may be half
+  const int last_lanes = (d & 255) ? 32 : 64;
+  float4 v[KEEP ? CH : 1];
+  float a = 0.f;
+  if (KEEP) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c < nch && (c + 1 < nch || lane < last_lanes)) v[c] = y4[c * 64];
+      a = fmaxf(fmaxf(a, fmaxf(fabsf(v[c].x), fabsf(v[c].y))), fmaxf(fabsf(v[c].z), fabsf(v[c].w)));
+    }
+  } else {
+    for (int c = 0; c < nch; ++c)
+      if (c + 1 < nch || lane < last_lanes) {
+        const float4 t = y4[c * 64];
+        a = fmaxf(fmaxf(a, fmaxf(fabsf(t.x), fabsf(t.y))), fmaxf(fabsf(t.z), fabsf(t.w)));
+      }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+  const float s = __fdiv_rn(__fmul_rn(clip, a), 7.0f);
+  const bool live = s > 0.f;
+  const float rinv = live ? __fdiv_rn(1.0f, s) : 0.f;
+  float e2 = 0.f, y2 = 0.f;
+  unsigned* crow = codes ? reinterpret_cast<unsigned*>(codes + row * d) + lane : nullptr;
+  auto quantise = [&](const float4& t, int c) {
+    const float y[4] = {t.x, t.y, t.z, t.w};
+    unsigned pack = 0u;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float q = rintf(__fmul_rn(y[e], rinv));
+      q = fminf(fmaxf(q, -7.f), 7.f);
+      if (!live) q = 0.f;
+      const float diff = y[e] - q * s;
+      e2 = fmaf(diff, diff, e2);
+      y2 = fmaf(y[e], y[e], y2);
+      pack |= ((unsigned)(int)q & 0xffu) << (8 * e);
+    }
+    if (crow) crow[c * 64] = pack;
+  };
+  if (KEEP) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+      if (c < nch && (c + 1 < nch || lane < last_lanes)) quantise(v[c], c);
+  } else {
+    for (int c = 0; c < nch; ++c)
+      if (c + 1 < nch || lane < last_lanes) quantise(y4[c * 64], c);
+  }
+  if (err) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      e2 += __shfl_xor(e2, o);
+      y2 += __shfl_xor(y2, o);
+    }
+  }
+  if (lane == 0) {
+    if (scales_out) scales_out[row] = s;
+    if (err) err[row] = make_float2(e2, y2);
+  }
+}
+
 // ---- per-token quantisation-quality figures of a materialised Y = X R ----------------------
 // (max-value "success" of "Evaluation ... on Channel Outliers"; Setup: symmetric per-token
 // quantisation clipped at a quantile, asymmetric quantisation for KV caches; Background:

@@ -118,3 +118,117 @@ def test_single_pass_d128_batched_with_row_stride_matches_the_contiguous_call():
         assert torch.equal(a, b)
     ref = oracle.fakequant_int4(ktgen.to_f64(Xc[1].cpu()), ktgen.to_f64(ktgen.bf16_round(R[1].cpu())))
     assert np.allclose(outs[0][1][1].numpy(), ref["scales"], rtol=1e-2)
+
+
+def _check_sampled_rows(X, R, rows, scales, codes, err, codes_given, err_given, scales_used):
+    """X [n][d] and R [d][d] on the device; rows: token indices; scales/codes/err: what the call that
+    computed its own scales returned for those rows; codes_given/err_given: what the call with
+    `scales_used` (the oracle's scales on these rows) handed in returned for them."""
+    Rb = ktgen.to_f64(ktgen.bf16_round(R)) if X.dtype == torch.bfloat16 else ktgen.to_f64(R)
+    Xr = ktgen.to_f64(X[torch.as_tensor(rows, device=X.device)])
+    o = oracle.fakequant_int4(Xr, Rb)
+    assert np.array_equal(scales_used, o["scales"])
+    assert np.allclose(scales, o["scales"], rtol=1e-4)
+    assert np.allclose(err, o["err"], rtol=2e-3)
+    t = (Xr @ Rb) / o["scales"].astype(np.float64)[:, None]
+    diff = codes_given.astype(np.int32) - o["codes"].astype(np.int32)
+    bad = diff != 0
+    assert np.abs(diff).max() <= 1
+    assert np.all(np.abs(np.abs(t[bad]) % 1.0 - 0.5) < 1e-3)
+    assert bad.mean() < 1e-3
+    assert np.allclose(err_given, o["err"], rtol=2e-3)
+    # own scales differ from the oracle's by rounding only: codes agree except next to a boundary
+    d2 = codes.astype(np.int32) - o["codes"].astype(np.int32)
+    assert np.abs(d2).max() <= 1 and (d2 != 0).mean() < 2e-3
+
+
+def _own_then_given(X, R, pick):
+    """Runs the entry point with its own scales, then with the oracle's scales on the picked rows
+    (problem, token) and its own elsewhere; returns both result sets (device tensors)."""
+    b, n, d = X.shape
+    ws = kt.Workspace()
+    so = torch.empty((b, n), device="cuda")
+    codes = torch.empty((b, n, d), dtype=torch.int8, device="cuda")
+    err = torch.empty((b, n, 2), device="cuda")
+    kt.kt_rotate_fakequant_int4(X, R, scales_out=so, codes=codes, err=err, workspace=ws)
+    sin = so.clone()
+    for p, rows in pick.items():
+        Rb = ktgen.to_f64(ktgen.bf16_round(R[p]))
+        o = oracle.fakequant_int4(ktgen.to_f64(X[p, torch.as_tensor(rows, device="cuda")]), Rb)
+        sin[p, torch.as_tensor(rows, device="cuda")] = torch.as_tensor(o["scales"], device="cuda")
+    codes2 = torch.empty_like(codes)
+    err2 = torch.empty_like(err)
+    kt.kt_rotate_fakequant_int4(X, R, scales_in=sin, codes=codes2, err=err2, workspace=ws)
+    torch.cuda.synchronize()
+    return so, codes, err, sin, codes2, err2
+
+
+def _check_picked(X, R, pick, res):
+    so, codes, err, sin, codes2, err2 = res
+    for p, rows in pick.items():
+        ix = torch.as_tensor(rows, device="cuda")
+        _check_sampled_rows(X[p], R[p], rows, so[p, ix].cpu().numpy(), codes[p, ix].cpu().numpy(),
+                            err[p, ix].cpu().numpy(), codes2[p, ix].cpu().numpy(), err2[p, ix].cpu().numpy(),
+                            sin[p, ix].cpu().numpy())
+
+
+def test_c3_full_size_sampled_rows_and_properties():
+    """d = 4096, n = 131072 (the benchmark's size; the fp32 staging buffer is filled eight times): sampled
+    rows against the oracle one by one, and over ALL rows what holds at any size: with clip = 1 the largest
+    code of a row is 7 in magnitude, no code leaves [-7, 7], every error is at most d (s/2)^2."""
+    X, R, cfg = ktgen.make_problem("C3", seed=0, device="cuda")
+    b, n, d = X.shape
+    rows = np.sort(np.random.default_rng(5).choice(n, size=40, replace=False))
+    rows[0], rows[-1] = 0, n - 1
+    pick = {0: rows}
+    res = _own_then_given(X, R, pick)
+    _check_picked(X, R, pick, res)
+    so, codes, err = res[0], res[1], res[2]
+    assert int(codes.min()) == -7 and int(codes.max()) == 7
+    assert bool((codes.abs().amax(dim=2) == 7).all())
+    assert bool((err[..., 0] <= d * (0.5 * so) ** 2 * 1.001).all()) and bool((err[..., 1] > 0).all())
+
+
+def test_rows_longer_than_the_register_budget_in_two_slices():
+    """d = 16384: a token row does not fit the row kernel's registers (it is read twice), and 4397 tokens
+    need a full staging slice of 4096 rows plus a ragged one."""
+    d, n = 16384, 4397
+    g = torch.Generator(device="cuda").manual_seed(12)
+    q, r = torch.linalg.qr(torch.randn((d, d), generator=g, device="cuda"))
+    R = (q * torch.sign(torch.diagonal(r)).unsqueeze(0)).contiguous().unsqueeze(0)
+    del q, r
+    X = ktgen.make_x(n, d, seed=4, outlier_cols=16, outlier_scale=50.0, t_frac=0.02, dtype="bf16", device="cuda").unsqueeze(0)
+    pick = {0: np.array([0, 1, 4095, 4096, 4300, n - 1])}
+    _check_picked(X, R, pick, _own_then_given(X, R, pick))
+
+
+def test_problems_grouped_by_the_staging_buffer():
+    """Five problems of 6000 tokens at d = 4096: two problems fit the staging buffer at a time, the last
+    launch pair takes the one that is left."""
+    batch, n, d = 5, 6000, 4096
+    X = ktgen.make_x(batch * n, d, seed=21, outlier_cols=8, outlier_scale=40.0, t_frac=0.03, dtype="bf16",
+                     device="cuda").reshape(batch, n, d)
+    R2 = torch.stack([ktgen.random_orthogonal(d, seed=60 + s, device="cuda") for s in range(2)])
+    R = R2[torch.arange(batch, device="cuda") % 2].contiguous()
+    pick = {0: np.array([0, 5999]), 1: np.array([17]), 2: np.array([0, 3000]), 3: np.array([5999]), 4: np.array([0, 1234, 5999])}
+    _check_picked(X, R, pick, _own_then_given(X, R, pick))
+
+
+def test_staged_path_with_row_stride_matches_the_contiguous_call():
+    n, d, batch = 700, 512, 2
+    Xfull = ktgen.make_x(n * batch, 640, seed=18, outlier_cols=3, outlier_scale=30.0, dtype="bf16").reshape(batch, n, 640).cuda()
+    Xv, Xc = Xfull[:, :, :d], Xfull[:, :, :d].contiguous()
+    R = torch.stack([ktgen.random_orthogonal(d, seed=70 + b) for b in range(batch)]).cuda()
+    outs = []
+    for X in (Xv, Xc):
+        codes = torch.empty((batch, n, d), dtype=torch.int8, device="cuda")
+        scales = torch.empty((batch, n), device="cuda")
+        err = torch.empty((batch, n, 2), device="cuda")
+        kt.kt_rotate_fakequant_int4(X, R, clip_ratio=0.9, scales_out=scales, codes=codes, err=err)
+        torch.cuda.synchronize()
+        outs.append((codes.cpu(), scales.cpu(), err.cpu()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    ref = oracle.fakequant_int4(ktgen.to_f64(Xc[1].cpu()), ktgen.to_f64(ktgen.bf16_round(R[1].cpu())), clip=0.9)
+    assert np.allclose(outs[0][1][1].numpy(), ref["scales"], rtol=1e-5)
+    assert (outs[0][0][1].numpy() != ref["codes"]).mean() < 2e-3
