@@ -196,7 +196,7 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
  *  clip_ratio in (0, 1]; 1 is the plain symmetric scale.
  *  scales_in  [batch][n] fp32 or NULL; if given it is used verbatim.
  *  scales_out [batch][n] fp32 or NULL.
- *  codes      [batch][n][d] int8, one code per byte in [-7, 7], or NULL.
+ *  codes      [batch][n][d] int8, one code per byte in [-7, 7], 16-byte aligned, or NULL.
  *  err        [batch][n][2] fp32 or NULL.
  *  A row with scale 0 gets codes 0.
  *  Workspace: kt_workspace_bytes(KT_OP_FAKEQUANT, ...).  It holds an fp32 staging buffer of at most

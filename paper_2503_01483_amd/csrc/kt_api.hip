@@ -974,7 +974,7 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
   if (!(clip_ratio > 0.f && clip_ratio <= 1.f))
     return fail(KT_ERR_INVALID_ARG, "clip_ratio must be in (0, 1]");
   if (!scales_out && !codes && !err) return fail(KT_ERR_INVALID_ARG, "no output requested");
-  if (reinterpret_cast<uintptr_t>(codes) & 3) return fail(KT_ERR_BAD_SHAPE, "codes must be 4-byte aligned");
+  if (reinterpret_cast<uintptr_t>(codes) & 15) return fail(KT_ERR_BAD_SHAPE, "codes must be 16-byte aligned");
   const QuantPlan p = plan_quant(batch, n, d, x_dtype);
   s = check_ws(workspace, workspace_bytes, p.total);
   if (s != KT_OK) return s;

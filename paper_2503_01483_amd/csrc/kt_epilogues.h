@@ -332,8 +332,8 @@ struct EpiAmax : EpiBase {
 // ---- fake-quant pass B: quantise the recomputed y ----------------------------------
 // Same orientation as the moment epilogue (token on the lane, features on the registers): the
 // scale and its reciprocal are taken once per token, the error sums accumulate in registers and
-// meet only the other half-wave, and the four consecutive features a lane owns per register
-// group leave as one 4-byte store of packed codes.  q = clamp(rint(y * (1/s)), -7, 7) in fp32;
+// meet only the other half-wave, and the codes leave as 16-byte stores (a lane and its partner in
+// the other half-wave exchange two packed words first).  q = clamp(rint(y * (1/s)), -7, 7) in fp32;
 // pe[(batch*P + p)*n_tokens + token] = {sum (y - q s)^2, sum y^2} over the wave's feature rows.
 template <class TL>
 struct EpiQuant : EpiBase {
@@ -357,6 +357,7 @@ struct EpiQuant : EpiBase {
 #pragma unroll
       for (int mb = 0; mb < TL::MB; ++mb) {
         if (m0 + f.m_block(mb) < d) {
+          unsigned pk[4];
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             unsigned pack = 0u;
@@ -371,8 +372,16 @@ struct EpiQuant : EpiBase {
               y2 = fmaf(y, y, y2);
               pack |= ((unsigned)(int)q & 0xffu) << (8 * e);
             }
-            if (codes && tv) *reinterpret_cast<unsigned*>(crow + m0 + f.m_of(mb, 4 * g)) = pack;
+            pk[g] = pack;
           }
+          // the lane and its partner (lane ^ 32) own alternate groups of four features: two words change
+          // hands, then the lower half-wave stores bytes 0..15 of the 32-feature block, the upper 16..31
+          const unsigned r0 = (unsigned)__shfl_xor((int)(f.half ? pk[0] : pk[2]), 32);
+          const unsigned r1 = (unsigned)__shfl_xor((int)(f.half ? pk[1] : pk[3]), 32);
+          uintx4 out;
+          if (f.half == 0) out = uintx4{pk[0], r0, pk[1], r1};
+          else out = uintx4{r0, pk[2], r1, pk[3]};
+          if (codes && tv) *reinterpret_cast<uintx4*>(crow + m0 + f.m_block(mb) + 16 * f.half) = out;
         }
       }
       if (err_part) {

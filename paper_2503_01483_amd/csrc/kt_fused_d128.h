@@ -464,7 +464,8 @@ __global__ __launch_bounds__(256) void quant_d128_kernel(const __bf16* __restric
       float e2 = 0.f, y2 = 0.f;
       int8_t* crow = codes + to * D;
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < 4; ++mb) {
+        unsigned pk[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           unsigned pack = 0u;
@@ -479,8 +480,18 @@ __global__ __launch_bounds__(256) void quant_d128_kernel(const __bf16* __restric
             y2 = fmaf(y, y, y2);
             pack |= ((unsigned)(int)q & 0xffu) << (8 * e);
           }
-          if (codes && tv) *reinterpret_cast<unsigned*>(crow + mb * 32 + 8 * g + 4 * half) = pack;
+          pk[g] = pack;
         }
+        // A lane owns features 8g + 4 half .. + 3 of the 32-feature block, its partner (lane ^ 32) the other
+        // four of each eight: swap two words so that each of the two holds 16 consecutive bytes of the
+        // token's row (lower half-wave bytes 0..15 of the block, upper 16..31) and stores them at once.
+        const unsigned r0 = (unsigned)__shfl_xor((int)(half ? pk[0] : pk[2]), 32);
+        const unsigned r1 = (unsigned)__shfl_xor((int)(half ? pk[1] : pk[3]), 32);
+        uintx4 out;
+        if (half == 0) out = uintx4{pk[0], r0, pk[1], r1};
+        else out = uintx4{r0, pk[2], r1, pk[3]};
+        if (codes && tv) *reinterpret_cast<uintx4*>(crow + mb * 32 + 16 * half) = out;
+      }
       if (err) {
         e2 += __shfl_xor(e2, 32);
         y2 += __shfl_xor(y2, 32);
