@@ -82,6 +82,9 @@ def test_argument_errors_are_synchronous():
     assert st == 1 and "clip" in kt.kt_last_error()
     st = L.kt_rotate_fakequant_int4(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.0, None, None, None, None, ws, 1 << 30, None)
     assert st == 1
+    st = L.kt_rotate_fakequant_int4(fake, 128, fake, 128, 1, 16, 128, 1, 1, 1.0, None, None, ctypes.c_void_p(0x1004), None,
+                                    ws, 1 << 30, None)
+    assert st == 2 and "16-byte" in kt.kt_last_error()
     # sizes beyond the documented limits
     st = L.kt_kurtosis_loss_grad(fake, 16512, fake, 16512, 1, 16, 16512, 1, 1, 0.0, fake, None, None, ws, 1 << 30, None)
     assert st == 2 and "16384" in kt.kt_last_error()
@@ -134,6 +137,9 @@ def test_workspace_queries_of_the_widened_ops():
     assert f(kt.KT_OP_QUANT_METRICS, 1, 1024, 256, kt.KT_BF16) >= 1024 * 256 * 4
     assert f(kt.KT_OP_FUSE_ROTATION, 1, 1000, 256, kt.KT_F32) >= 1000 * 256 * 4
     assert f(kt.KT_OP_SENSITIVITY, 1, 1, 128, kt.KT_F32) > 0
+    # fake-quant: the fp32 staging slice of rotated rows is bounded (256 MiB), whatever n is
+    small, large = f(kt.KT_OP_FAKEQUANT, 1, 1 << 14, 4096, kt.KT_BF16), f(kt.KT_OP_FAKEQUANT, 1, 1 << 20, 4096, kt.KT_BF16)
+    assert small >= (1 << 14) * 4096 * 4 and large - small < (1 << 20) * 1200
 
 
 def test_bench_refuses_more_than_one_gpu():
