@@ -148,7 +148,9 @@ kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R
  *  R_lowp   [batch][d][d] bf16 copy of the new R (nearest-even), or NULL.
  *  ortho_err[batch] fp32: max_ij |(R+^T R+ - I)_ij| of the result, or NULL (skips one GEMM).
  *  info     [batch] int32: number of iterations used, or -1 if the iteration did not
- *           converge within the library's limit (R is then still written), or NULL.
+ *           converge within the library's limit, or NULL.  A step that did not converge is
+ *           rejected: R comes back unchanged, R_lowp is the bf16 copy of that unchanged R, and
+ *           ortho_err is unspecified.
  */
 kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d,
                          float lr, float* ortho_err, int32_t* info,

@@ -513,7 +513,8 @@ __global__ __launch_bounds__(256) void cayley_update_kernel(const float* __restr
   if (threadIdx.x == 0) atomicMax(&dl[it], umax(umax(sh[0], sh[1]), umax(sh[2], sh[3])));
 }
 
-// Cayley wrap-up: R = Zt^T (and its bf16 copy), info = iterations used or -1.
+// Cayley wrap-up: R = Zt^T (and its bf16 copy), info = iterations used or -1.  An iteration that did
+// not converge is rejected as a whole: R stays as it is and the bf16 copy is taken from it.
 __global__ __launch_bounds__(256) void cayley_finish_kernel(const float* __restrict__ Zt, int d,
                                                             float* __restrict__ R,
                                                             __bf16* __restrict__ R_lowp,
@@ -524,27 +525,31 @@ __global__ __launch_bounds__(256) void cayley_finish_kernel(const float* __restr
   const int64_t bo = (int64_t)blockIdx.z * d * d;
   const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  int used = -1;  // the same scan in every thread: at most max_iters words, all cache hits
+  for (int k = 0; k < max_iters; ++k) {
+    if (cayley_converged(delta + (int64_t)blockIdx.z * max_iters, k, tol)) { used = k + 1; break; }
+  }
+  if (used > 0) {
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int rr = ty + 8 * k;
-    tz[rr][tx] = Zt[bo + (int64_t)(j0 + rr) * d + i0 + tx];
+    for (int k = 0; k < 4; ++k) {
+      const int rr = ty + 8 * k;
+      tz[rr][tx] = Zt[bo + (int64_t)(j0 + rr) * d + i0 + tx];
+    }
   }
   __syncthreads();
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const int rr = ty + 8 * k;
     const int64_t idx = bo + (int64_t)(i0 + rr) * d + j0 + tx;
-    const float v = tz[tx][rr];
-    R[idx] = v;
-    if (R_lowp) R_lowp[idx] = (__bf16)v;
-  }
-  if (info && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-    int used = -1;
-    for (int k = 0; k < max_iters; ++k) {
-      if (cayley_converged(delta + (int64_t)blockIdx.z * max_iters, k, tol)) { used = k + 1; break; }
+    if (used > 0) {
+      const float v = tz[tx][rr];
+      R[idx] = v;
+      if (R_lowp) R_lowp[idx] = (__bf16)v;
+    } else if (R_lowp) {
+      R_lowp[idx] = (__bf16)R[idx];
     }
-    info[blockIdx.z] = used;
   }
+  if (info && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) info[blockIdx.z] = used;
 }
 
 // Diagonal of Zt Zt^T - I: | sum_k Zt[m][k]^2 - 1 | summed in fp64, folded into err[batch]

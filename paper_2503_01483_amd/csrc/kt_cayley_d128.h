@@ -236,14 +236,15 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
     __syncthreads();
   }
 
-  // Zt -> bufA, then R = Zt^T with coalesced 16-byte stores
+  // Zt -> bufA, then R = Zt^T with coalesced 16-byte stores.  An iteration that did not converge is
+  // rejected as a whole: R (and its bf16 copy) come out as they went in.
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        *reinterpret_cast<float*>(bufA + c128_addr(m_of(i, r), n_of(j))) = zt[i][j][r];
+        *reinterpret_cast<float*>(bufA + c128_addr(m_of(i, r), n_of(j))) = used < 0 ? rt[i][j][r] : zt[i][j][r];
   __syncthreads();
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {

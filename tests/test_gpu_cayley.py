@@ -70,13 +70,16 @@ def test_zero_step_and_radial_gradient():
     assert float((Rn - R).abs().max()) < 1e-6
 
 
-def test_divergent_step_is_flagged_not_hung():
-    # (lr/2)||A|| >> 1: the fixed point does not contract; the library must say so
-    d = 128
-    R = torch.eye(d).unsqueeze(0)
+@pytest.mark.parametrize("d", [128, 256, 1024])   # single-workgroup kernel, fp32 GEMM path, three-term bf16 path
+def test_divergent_step_is_flagged_and_rejected(d):
+    # (lr/2)||A|| >> 1: the fixed point does not contract; the library must say so, and R (with its
+    # bf16 copy) must come back as it went in rather than as the last, meaningless iterate
+    R = ktgen.random_orthogonal(d, seed=4).unsqueeze(0)
     G = torch.randn((1, d, d), generator=torch.Generator().manual_seed(2))
-    _, _, _, info = _run(R, G, 10.0)
+    Rn, lowp, _, info = _run(R, G, 10.0)
     assert info[0] == -1
+    assert torch.equal(Rn, R)
+    assert torch.equal(lowp, R.to(torch.bfloat16))
 
 
 def test_teacher_forced_steps_c1():
