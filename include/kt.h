@@ -202,7 +202,7 @@ kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int
  *  err        [batch][n][2] fp32 or NULL.
  *  A row with scale 0 gets codes 0.
  *  Workspace: kt_workspace_bytes(KT_OP_FAKEQUANT, ...).  It holds an fp32 staging buffer of at most
- *  256 MiB: when the scales are computed here, y is rotated once, a slice of token rows at a time,
+ *  1 GiB: when the scales are computed here, y is rotated once, a slice of token rows at a time,
  *  and a row kernel takes the maximum and quantises the staged values (one GEMM pass instead of a
  *  second one that recomputes y).  With scales_in the codes come straight out of the GEMM's registers.
  *  d = 128 in bf16 is a single fused pass with no staging.
@@ -231,7 +231,8 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
  *             the workspace).  Every output pointer may be NULL.
  * Y is materialised (this is an evaluation tool, not the training step): one GEMM pass, then one
  * workgroup per token with the row in LDS (radix select for the quantile).  d <= 8192.
- * Workspace: kt_workspace_bytes(KT_OP_QUANT_METRICS, ...) (sized for Y == NULL).
+ * Workspace: kt_workspace_bytes(KT_OP_QUANT_METRICS, ...) (sized for Y == NULL: the rotated rows then
+ * pass through an fp32 staging slice of at most 1 GiB, a few problems or token rows at a time).
  */
 kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int64_t ldr,
                                   int64_t batch, int64_t n, int64_t d,

@@ -261,7 +261,17 @@ struct QuantPlan {
   size_t o_rt, o_amax, o_scales, o_errpart, o_y, total;
 };
 
-constexpr int64_t kQuantStageBytes = (int64_t)256 << 20;  // 64 MiB .. 4 GiB measured alike at d = 4096
+// d = 4096, n = 131072: fake-quant measured alike from 64 MiB to 4 GiB; the quantisation figures, whose row
+// kernel is one workgroup per token, lose 7 % at 256 MiB and nothing at 1 GiB
+constexpr int64_t kQuantStageBytes = (int64_t)1 << 30;
+
+// How many whole problems, or how many token rows of one problem, an fp32 staging buffer of at most
+// kQuantStageBytes takes per launch pair (rotation GEMM + row kernel).
+static void stage_slices(int64_t batch, int64_t n, int64_t d, int64_t* problems, int64_t* rows) {
+  const int64_t cap = kQuantStageBytes / (4 * d) / 256 * 256;  // >= 16384 token rows at d <= 16384
+  *rows = n < cap ? n : cap;
+  *problems = n <= cap ? (cap / n < batch ? cap / n : batch) : 1;
+}
 
 static QuantPlan plan_quant(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
   QuantPlan p;
@@ -282,9 +292,7 @@ static QuantPlan plan_quant(int64_t batch, int64_t n, int64_t d, kt_dtype xdt) {
   p.o_amax = c.take((size_t)batch * p.P * n * 4);
   p.o_scales = c.take((size_t)batch * n * 4);
   p.o_errpart = c.take((size_t)batch * p.P * n * 8);
-  int64_t cap = kQuantStageBytes / (4 * d) / 256 * 256;  // >= 4096 token rows at d <= 16384
-  p.stage_rows = n < cap ? n : cap;
-  p.stage_problems = n <= cap ? (cap / n < batch ? cap / n : batch) : 1;
+  stage_slices(batch, n, d, &p.stage_problems, &p.stage_rows);
   p.o_y = c.take((size_t)p.stage_problems * p.stage_rows * d * 4);
   p.total = c.off;
   return p;
@@ -827,7 +835,11 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
       return plan_loss_grad(batch, n, d, x_dtype, true).total;
     case KT_OP_QUANT_METRICS:
       if (n < 1) return 0;
-      return round_up(batch * d * d * (x_dtype == KT_F32 ? 4 : 2), 256) + (size_t)batch * n * d * 4;
+      {  // R^T and, when the caller does not ask for Y, an fp32 staging slice of it
+        int64_t sp, sr;
+        stage_slices(batch, n, d, &sp, &sr);
+        return round_up(batch * d * d * (x_dtype == KT_F32 ? 4 : 2), 256) + (size_t)sp * sr * d * 4;
+      }
     case KT_OP_FUSE_ROTATION:  // n = the other dimension k of the weight
       if (n < 1) return 0;
       return round_up(d * d * 4, 256) + (size_t)n * d * 4;
@@ -1014,7 +1026,11 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
   if (d > 8192) return fail(KT_ERR_NOT_SUPPORTED, "quantisation metrics keep a token row in LDS: d <= 8192");
   const bool fp32 = x_dtype == KT_F32;
   const size_t rt_bytes = (size_t)round_up(batch * d * d * (fp32 ? 4 : 2), 256);
-  const size_t need = rt_bytes + (Y ? 0 : (size_t)batch * n * d * 4);
+  // With Y wanted the whole rotation is one launch pair into the caller's buffer; without it Y passes through
+  // a bounded staging slice, some problems or some token rows of one problem at a time.
+  int64_t sp = batch, sr = n;
+  if (!Y) stage_slices(batch, n, d, &sp, &sr);
+  const size_t need = rt_bytes + (Y ? 0 : (size_t)sp * sr * d * 4);
   s = check_ws(workspace, workspace_bytes, need);
   if (s != KT_OK) return s;
   char* ws = static_cast<char*>(workspace);
@@ -1027,21 +1043,29 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
     using T = decltype(t_tag);
     using TL = decltype(tile_tag);
     T* RT = reinterpret_cast<T*>(ws);
+    const T* Xp = static_cast<const T*>(X);
     if (!prep_rt<T>(R, ldr, r_dtype, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
-    EpiStore<TL> e;
-    e.C = Yb; e.ldc = d; e.batch_stride = n * d; e.split_stride = 0; e.M = (int)n; e.N = (int)d;
-    if (!launch_gemm<TL>(static_cast<const T*>(X), ldx, n * ldx, (int)n, RT, d, d * d, (int)d, d, 0, (int)batch, e,
-                         st))
-      return fail(KT_ERR_DEVICE, "rotation GEMM launch failed");
     if (success) {
       hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<unsigned*>(success),
                          2 * batch, 0u);
     }
-    hipLaunchKernelGGL((quant_metrics_row_kernel<T>), dim3((unsigned)n, (unsigned)batch), dim3(256),
-                       (size_t)d * 4, st, Yb, static_cast<const T*>(X), ldx, n * ldx, (int)n, (int)d,
-                       (double)quantile, amax, threshold, err_sym, err_asym,
-                       reinterpret_cast<unsigned long long*>(success));
-    if (!launch_ok()) return fail(KT_ERR_DEVICE, "metrics kernel launch failed");
+    for (int64_t b0 = 0; b0 < batch; b0 += sp) {
+      const int64_t nb = batch - b0 < sp ? batch - b0 : sp;
+      for (int64_t t0 = 0; t0 < n; t0 += sr) {
+        const int64_t nt = n - t0 < sr ? n - t0 : sr, row0 = b0 * n + t0;
+        EpiStore<TL> e;
+        e.C = Yb; e.ldc = d; e.batch_stride = nt * d; e.split_stride = 0; e.M = (int)nt; e.N = (int)d;
+        if (!launch_gemm<TL>(Xp + row0 * ldx, ldx, n * ldx, (int)nt, RT + b0 * d * d, d, d * d, (int)d, d, 0, (int)nb,
+                             e, st))
+          return fail(KT_ERR_DEVICE, "rotation GEMM launch failed");
+        hipLaunchKernelGGL((quant_metrics_row_kernel<T>), dim3((unsigned)nt, (unsigned)nb), dim3(256),
+                           (size_t)d * 4, st, Yb, Xp + row0 * ldx, ldx, n * ldx, (int)nt, (int)d, (double)quantile,
+                           amax ? amax + 2 * row0 : nullptr, threshold ? threshold + row0 : nullptr,
+                           err_sym ? err_sym + 2 * row0 : nullptr, err_asym ? err_asym + 2 * row0 : nullptr,
+                           success ? reinterpret_cast<unsigned long long*>(success) + b0 : nullptr);
+        if (!launch_ok()) return fail(KT_ERR_DEVICE, "metrics kernel launch failed");
+      }
+    }
     return KT_OK;
   };
   if (fp32) return rotate(float{}, TF{});

@@ -137,9 +137,9 @@ def test_workspace_queries_of_the_widened_ops():
     assert f(kt.KT_OP_QUANT_METRICS, 1, 1024, 256, kt.KT_BF16) >= 1024 * 256 * 4
     assert f(kt.KT_OP_FUSE_ROTATION, 1, 1000, 256, kt.KT_F32) >= 1000 * 256 * 4
     assert f(kt.KT_OP_SENSITIVITY, 1, 1, 128, kt.KT_F32) > 0
-    # fake-quant: the fp32 staging slice of rotated rows is bounded (256 MiB), whatever n is
+    # fake-quant: the fp32 staging slice of rotated rows is bounded (1 GiB), whatever n is
     small, large = f(kt.KT_OP_FAKEQUANT, 1, 1 << 14, 4096, kt.KT_BF16), f(kt.KT_OP_FAKEQUANT, 1, 1 << 20, 4096, kt.KT_BF16)
-    assert small >= (1 << 14) * 4096 * 4 and large - small < (1 << 20) * 1200
+    assert small >= (1 << 14) * 4096 * 4 and large - small < (1 << 20) * 1200 + (1 << 30)
 
 
 def test_bench_refuses_more_than_one_gpu():

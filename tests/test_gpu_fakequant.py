@@ -173,7 +173,7 @@ def _check_picked(X, R, pick, res):
 
 
 def test_c3_full_size_sampled_rows_and_properties():
-    """d = 4096, n = 131072 (the benchmark's size; the fp32 staging buffer is filled eight times): sampled
+    """d = 4096, n = 131072 (the benchmark's size; the fp32 staging buffer is filled twice): sampled
     rows against the oracle one by one, and over ALL rows what holds at any size: with clip = 1 the largest
     code of a row is 7 in magnitude, no code leaves [-7, 7], every error is at most d (s/2)^2."""
     X, R, cfg = ktgen.make_problem("C3", seed=0, device="cuda")
@@ -190,27 +190,27 @@ def test_c3_full_size_sampled_rows_and_properties():
 
 
 def test_rows_longer_than_the_register_budget_in_two_slices():
-    """d = 16384: a token row does not fit the row kernel's registers (it is read twice), and 4397 tokens
-    need a full staging slice of 4096 rows plus a ragged one."""
-    d, n = 16384, 4397
+    """d = 16384: a token row does not fit the row kernel's registers (it is read twice), and 16685 tokens
+    need a full staging slice of 16384 rows plus a ragged one."""
+    d, n = 16384, 16685
     g = torch.Generator(device="cuda").manual_seed(12)
     q, r = torch.linalg.qr(torch.randn((d, d), generator=g, device="cuda"))
     R = (q * torch.sign(torch.diagonal(r)).unsqueeze(0)).contiguous().unsqueeze(0)
     del q, r
     X = ktgen.make_x(n, d, seed=4, outlier_cols=16, outlier_scale=50.0, t_frac=0.02, dtype="bf16", device="cuda").unsqueeze(0)
-    pick = {0: np.array([0, 1, 4095, 4096, 4300, n - 1])}
+    pick = {0: np.array([0, 1, 16383, 16384, 16500, n - 1])}
     _check_picked(X, R, pick, _own_then_given(X, R, pick))
 
 
 def test_problems_grouped_by_the_staging_buffer():
-    """Five problems of 6000 tokens at d = 4096: two problems fit the staging buffer at a time, the last
+    """Five problems of 30000 tokens at d = 4096: two problems fit the staging buffer at a time, the last
     launch pair takes the one that is left."""
-    batch, n, d = 5, 6000, 4096
+    batch, n, d = 5, 30000, 4096
     X = ktgen.make_x(batch * n, d, seed=21, outlier_cols=8, outlier_scale=40.0, t_frac=0.03, dtype="bf16",
                      device="cuda").reshape(batch, n, d)
     R2 = torch.stack([ktgen.random_orthogonal(d, seed=60 + s, device="cuda") for s in range(2)])
     R = R2[torch.arange(batch, device="cuda") % 2].contiguous()
-    pick = {0: np.array([0, 5999]), 1: np.array([17]), 2: np.array([0, 3000]), 3: np.array([5999]), 4: np.array([0, 1234, 5999])}
+    pick = {0: np.array([0, n - 1]), 1: np.array([17]), 2: np.array([0, 3000]), 3: np.array([n - 1]), 4: np.array([0, 1234, n - 1])}
     _check_picked(X, R, pick, _own_then_given(X, R, pick))
 
 

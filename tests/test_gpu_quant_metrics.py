@@ -81,3 +81,33 @@ def test_learned_rotation_direction_on_outlier_channels():
     rel0 = g0["err_sym"][0][:, 0].sum() / g0["err_sym"][0][:, 1].sum()
     rel1 = g1["err_sym"][0][:, 0].sum() / g1["err_sym"][0][:, 1].sum()
     assert rel1 < rel0
+
+
+@pytest.mark.parametrize("n,d,batch", [(66000, 4096, 1), (30000, 4096, 5)])
+def test_without_y_the_rows_pass_through_a_bounded_staging_slice(n, d, batch):
+    """No Y asked for: 65536 token rows (or two problems) per launch pair at d = 4096.  Every figure must be
+    what the call that returns Y gives, and sampled rows of that Y reproduce them in the oracle."""
+    X = ktgen.make_x(n * batch, d, seed=31, outlier_cols=6, outlier_scale=30.0, t_frac=0.03, dtype="bf16",
+                     device="cuda").reshape(batch, n, d)
+    R2 = torch.stack([ktgen.random_orthogonal(d, seed=80 + s, device="cuda") for s in range(2)])
+    R = R2[torch.arange(batch, device="cuda") % 2].contiguous()
+    full = dict(Y=torch.empty((batch, n, d), device="cuda"))
+    outs = []
+    for extra in (full, {}):
+        o = dict(amax=torch.empty((batch, n, 2), device="cuda"), threshold=torch.empty((batch, n), device="cuda"),
+                 err_sym=torch.empty((batch, n, 2), device="cuda"), err_asym=torch.empty((batch, n, 2), device="cuda"),
+                 success=torch.full((batch,), -1, dtype=torch.int64, device="cuda"))
+        kt.kt_rotate_quant_metrics(X, R, quantile=0.98, **o, **extra)
+        torch.cuda.synchronize()
+        outs.append(o)
+    for k in outs[0]:
+        assert torch.equal(outs[0][k], outs[1][k]), k
+    assert kt.kt_workspace_bytes(kt.KT_OP_QUANT_METRICS, batch, n, d, kt.KT_BF16) < batch * d * d * 2 + (1025 << 20)
+    for b, rows in ((0, [0, min(65535, n - 2), 65536 % n, n - 1]), (batch - 1, [5, n - 1])):   # both sides of a slice boundary
+        ix = torch.as_tensor(rows, device="cuda")
+        o = oracle.quant_metrics(ktgen.to_f64(X[b, ix]), ktgen.to_f64(ktgen.bf16_round(R[b])), float(np.float32(0.98)),
+                                 Y=full["Y"][b, ix].cpu().numpy())
+        assert np.array_equal(outs[1]["threshold"][b, ix].cpu().numpy(), o["thr"])
+        assert np.array_equal(outs[1]["amax"][b, ix].cpu().numpy(), o["amax"])
+        assert np.allclose(outs[1]["err_sym"][b, ix].cpu().numpy(), o["err_sym"], rtol=2e-6, atol=0)
+        assert np.allclose(outs[1]["err_asym"][b, ix].cpu().numpy(), o["err_asym"], rtol=2e-6, atol=0)
