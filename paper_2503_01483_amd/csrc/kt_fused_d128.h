@@ -373,7 +373,8 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
 
 // ---- single-pass rotate + int4 fake-quant for d = 128 (bf16) -------------------------------
 // A lane pair holds a whole rotated token row, so the row maximum, the scale, the codes and the
-// error sums all come out of ONE pass over X (the generic path rotates twice: maxima, then codes).
+// error sums all come out of ONE pass over X (the generic path parks the rotated rows in an fp32
+// staging buffer between the GEMM and a row kernel).
 // Every wave is on its own: 32-token tiles, its rows staged through 8 KiB of private LDS (loads of
 // the next tile in flight), R^T fragments in accumulation registers, no workgroup barrier.
 // Arithmetic identical to the generic path: s = (clip amax) / 7, q = clamp(rint(y (1/s)), -7, 7).
