@@ -160,9 +160,11 @@ def main():
     kt.kt_profile_enable(0)
     if args.op == "sensitivity":
         ms = 1e3 * elapsed / args.steps
-        evals = float(n) * d * 4 * 32          # 4 sweeps x 32 candidate slots per element
-        lane_ops = evals * 7                     # mul, rint, min, max, fma, fma + the fp64 flush share
-        peak = 256 * 4 * 16 * 2.4e9 / 1e12       # fp32 vector lanes x clock, one operation per lane and cycle
+        evals = float(n) * d * (3 * 32 + 4)      # three sweeps of 32 candidate steps, one of 1 + 3 fractions
+        lane_ops = evals * 5                     # per candidate: mul, rint, clamp (med3), fma, fma
+        # 256 CUs x 4 SIMDs x 32 fp32 lanes x 2.4 GHz, one operation per lane and cycle (the published 157.3 TFLOP/s
+        # counts a fused multiply-add as two; measured: a wave64 instruction every 2.4-2.6 cycles per SIMD)
+        peak = 256 * 4 * 32 * 2.4e9 / 1e12
         print(json.dumps({
             "metric": "elements/sec through kt_quant_sensitivity (optimal int4 step + sensitivity of one tensor)",
             "value": round(float(n) * d * args.steps / elapsed, 1), "unit": "elements/s", "n_gpus": 1,

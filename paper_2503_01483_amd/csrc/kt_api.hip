@@ -1162,7 +1162,8 @@ kt_status kt_quant_sensitivity(const float* Y, int64_t count, int32_t bits, cons
   if (!launch_ok()) return fail(KT_ERR_DEVICE, "sensitivity set-up launch failed");
   for (int round = 0; round < 4; ++round) {
     const int ns = round < 3 ? kSensSteps : 1 + n_alpha;
-    hipLaunchKernelGGL(sens_sweep_kernel, dim3(nblocks), dim3(256), 0, st, Y, count, stt, ns, L, part);
+    hipLaunchKernelGGL(sens_sweep_kernel, dim3(nblocks, (unsigned)ceil_div(ns, kSensPerBlock)), dim3(256), 0, st, Y, count, stt,
+                       ns, L, part);
     hipLaunchKernelGGL(sens_select_kernel, dim3(1), dim3(256), 0, st, part, nblocks, ns, count, round, L, stt, dst,
                        alphas, (int)n_alpha, out, gamma);
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "sensitivity sweep launch failed");

@@ -880,44 +880,56 @@ __global__ __launch_bounds__(256) void sens_amax_kernel(const float* __restrict_
 // q = clamp(rint(y (1/s)), -L, L) in fp32, error in fp32 per element, fp64 across elements of a thread
 // every 64 elements and across the block.
 constexpr int kSensSteps = 32;
+// grid = (blocks, kSensSteps / kSensPerBlock): a workgroup evaluates kSensPerBlock of the candidates, which keeps
+// it under 128 registers (four waves per SIMD: a single wave issues a vector instruction only every ~5 cycles).
+constexpr int kSensPerBlock = 16;
 __global__ __launch_bounds__(256) void sens_sweep_kernel(const float* __restrict__ y, int64_t count,
                                                          const float* __restrict__ steps, int ns, float L,
                                                          double* __restrict__ part) {
   __shared__ double sh[4];
-  __shared__ float s_s[kSensSteps], s_r[kSensSteps];
-  if (threadIdx.x < kSensSteps) {
-    const float s = threadIdx.x < ns ? steps[threadIdx.x] : 0.f;
-    s_s[threadIdx.x] = s;
-    s_r[threadIdx.x] = s > 0.f ? __fdiv_rn(1.0f, s) : 0.f;
+  const int j0 = blockIdx.y * kSensPerBlock;
+  // candidate steps and reciprocals in registers; fp32 partial sums over 64 elements, then fp64
+  float cs[kSensPerBlock], cr[kSensPerBlock];
+#pragma unroll
+  for (int j = 0; j < kSensPerBlock; ++j) {
+    const float s = j0 + j < ns ? steps[j0 + j] : 0.f;
+    cs[j] = s;
+    cr[j] = s > 0.f ? __fdiv_rn(1.0f, s) : 0.f;
   }
-  __syncthreads();
-  double acc[kSensSteps];
+  double acc[kSensPerBlock];
 #pragma unroll
-  for (int j = 0; j < kSensSteps; ++j) acc[j] = 0.0;
-  float facc[kSensSteps];
+  for (int j = 0; j < kSensPerBlock; ++j) acc[j] = 0.0;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t base = (int64_t)blockIdx.x * 256 + threadIdx.x; base < count; base += 64 * stride) {
+    float facc[kSensPerBlock];
 #pragma unroll
-  for (int j = 0; j < kSensSteps; ++j) facc[j] = 0.f;
-  int pending = 0;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
-    const float v = y[i];
+    for (int j = 0; j < kSensPerBlock; ++j) facc[j] = 0.f;
+    const int64_t left = (count - base + stride - 1) / stride;  // elements of this thread from base on
+    const int trips = left < 64 ? (int)left : 64;
+    const float* yp = y + base;
+    float vnext = *yp;  // the next element is requested before the candidates of this one are evaluated
+#pragma unroll 1
+    for (int k = 0; k < trips; ++k) {
+      const float v = vnext;
+      yp += stride;
+      if (k + 1 < trips) vnext = *yp;
 #pragma unroll
-    for (int j = 0; j < kSensSteps; ++j) {
-      float q = rintf(__fmul_rn(v, s_r[j]));
-      q = fminf(fmaxf(q, -L), L);
-      const float dlt = v - q * s_s[j];
-      facc[j] = fmaf(dlt, dlt, facc[j]);
+      for (int j = 0; j < kSensPerBlock; ++j) {
+        float q = rintf(__fmul_rn(v, cr[j]));
+        q = __builtin_amdgcn_fmed3f(q, -L, L);  // clamp in one instruction (q is finite)
+        const float dlt = v - q * cs[j];
+        facc[j] = fmaf(dlt, dlt, facc[j]);
+      }
     }
-    if (++pending == 64) {
 #pragma unroll
-      for (int j = 0; j < kSensSteps; ++j) { acc[j] += (double)facc[j]; facc[j] = 0.f; }
-      pending = 0;
-    }
+    for (int j = 0; j < kSensPerBlock; ++j) acc[j] += (double)facc[j];
   }
 #pragma unroll
-  for (int j = 0; j < kSensSteps; ++j) acc[j] += (double)facc[j];
-  for (int j = 0; j < ns; ++j) {
-    const double t = block_dsum_fast_256(acc[j], sh);
-    if (threadIdx.x == 0) part[(int64_t)blockIdx.x * kSensSteps + j] = t;
+  for (int j = 0; j < kSensPerBlock; ++j) {
+    if (j0 + j < ns) {  // uniform
+      const double t = block_dsum_fast_256(acc[j], sh);
+      if (threadIdx.x == 0) part[(int64_t)blockIdx.x * kSensSteps + j0 + j] = t;
+    }
   }
 }
 
