@@ -53,3 +53,46 @@ def test_captured_step_replays_like_the_eager_step(name, n, batch, adam):
         if adam:
             assert torch.equal(cap["M"], eager["M"]) and torch.equal(cap["v"], eager["v"])
         _ = (X[:, :64].float() ** 2).sum().item()    # unrelated eager work and a sync between replays
+
+
+@pytest.mark.parametrize("n,d,batch", [(3000, 512, 1), (2500, 128, 3)])
+def test_captured_evaluation_calls_replay_like_eager_ones(n, d, batch):
+    """Fake-quant (scales computed in the call, and handed in), quantisation figures and the Hadamard rows in
+    one captured graph; the inputs change between replays, every replay must match the eager calls."""
+    X = ktgen.make_x(n * batch, d, seed=4, outlier_cols=3, outlier_scale=30.0, dtype="bf16", device="cuda").reshape(batch, n, d)
+    R = torch.stack([ktgen.random_orthogonal(d, seed=30 + b, device="cuda") for b in range(batch)])
+
+    def state():
+        return dict(ws=kt.Workspace("cuda"), so=torch.zeros((batch, n), device="cuda"),
+                    codes=torch.zeros((batch, n, d), dtype=torch.int8, device="cuda"), err=torch.zeros((batch, n, 2), device="cuda"),
+                    codes2=torch.zeros((batch, n, d), dtype=torch.int8, device="cuda"), thr=torch.zeros((batch, n), device="cuda"),
+                    es=torch.zeros((batch, n, 2), device="cuda"), succ=torch.zeros(batch, dtype=torch.int64, device="cuda"),
+                    H=torch.zeros((n, d), dtype=torch.bfloat16, device="cuda"))
+
+    def calls(s, Xin):
+        kt.kt_rotate_fakequant_int4(Xin, R, scales_out=s["so"], codes=s["codes"], err=s["err"], workspace=s["ws"])
+        kt.kt_rotate_fakequant_int4(Xin, R, scales_in=s["so"], codes=s["codes2"], workspace=s["ws"])
+        kt.kt_rotate_quant_metrics(Xin, R, quantile=0.98, threshold=s["thr"], err_sym=s["es"], success=s["succ"], workspace=s["ws"])
+        kt.kt_hadamard_rows(Xin[0], out=s["H"])
+
+    eager, cap = state(), state()
+    Xc = X.clone()
+    calls(eager, Xc)
+    calls(cap, Xc)                     # warm-up outside the capture (function attributes, workspace size)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            calls(cap, Xc)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        Xc.copy_(torch.roll(X, rep + 1, dims=1))     # new input in the captured buffer
+        torch.cuda.synchronize()
+        g.replay()
+        calls(eager, Xc)
+        torch.cuda.synchronize()
+        for k in ("so", "codes", "err", "codes2", "thr", "es", "succ", "H"):
+            assert torch.equal(cap[k], eager[k]), (rep, k)
+        _ = (X[:, :64].float() ** 2).sum().item()    # unrelated eager work and a sync between replays
