@@ -104,3 +104,14 @@ def test_teacher_forced_steps_c1():
         losses.append(o["loss"])
         Ro = Rnext
     assert losses[2] < losses[0]
+
+
+@pytest.mark.parametrize("d", [128, 256, 1024])
+def test_non_finite_gradient_never_reaches_the_rotation(d):
+    # a NaN in the gradient (say, from a NaN activation): the fixed point cannot converge on it, the call reports
+    # -1 and leaves R untouched, so a training loop stalls visibly instead of filling R with NaNs
+    R = ktgen.random_orthogonal(d, seed=7).unsqueeze(0)
+    G = torch.randn((1, d, d), generator=torch.Generator().manual_seed(3)) * 0.1
+    G[0, 5, 9] = float("nan")
+    Rn, lowp, _, info = _run(R, G, 0.01)
+    assert info[0] == -1 and torch.equal(Rn, R) and torch.equal(lowp, R.to(torch.bfloat16))
