@@ -1,0 +1,66 @@
+"""Seeded random shapes inside the documented limits (hidden size, token count, problem count, row stride,
+dtype), the three headline entry points on each against the oracle: loss, per-row kurtosis, gradient,
+Cayley step, fake-quant scales / codes / errors.  Tolerances as in the dedicated tests."""
+import numpy as np
+import pytest
+import torch
+
+import ktgen
+import oracle
+import paper_2503_01483_amd as kt
+from parity_util import rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        d = int(rng.choice([128, 256, 384, 512, 640, 768, 1024, 1280, 2048]))
+        n = int(rng.integers(1, 3000)) if rng.random() < 0.8 else int(rng.integers(4000, 9500))
+        if d >= 1024:
+            n = min(n, 2000)
+        batch = int(rng.choice([1, 1, 2, 3]))
+        align = 8 if dtype == "bf16" else 4
+        pad = int(rng.choice([0, 0, align, 5 * align, 64]))
+        out.append((dtype, d, n, batch, pad, int(rng.integers(0, 10000))))
+    return out
+
+
+@pytest.mark.parametrize("dtype,d,n,batch,pad,seed", _cases(2024, 14))
+def test_random_shape(dtype, d, n, batch, pad, seed):
+    Xf = torch.stack([ktgen.make_x(n, d + pad, seed=seed + b, outlier_cols=3, outlier_scale=40.0, t_frac=0.03, dtype=dtype)
+                      for b in range(batch)]).cuda()
+    X = Xf[:, :, :d]                                   # row stride d + pad
+    R = torch.stack([ktgen.random_orthogonal(d, seed=seed + 100 + b) for b in range(batch)]).cuda()
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    ws = kt.Workspace()
+    rk = torch.empty((batch, n), device="cuda")
+    dR = torch.empty((batch, d, d), device="cuda")
+    loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
+    so = torch.empty((batch, n), device="cuda")
+    codes = torch.empty((batch, n, d), dtype=torch.int8, device="cuda")
+    err = torch.empty((batch, n, 2), device="cuda")
+    kt.kt_rotate_fakequant_int4(X, R, clip_ratio=0.95, scales_out=so, codes=codes, err=err, workspace=ws)
+    Rn = R.clone()
+    oe = torch.zeros(batch, device="cuda")
+    kt.kt_cayley_step(Rn, dR, 0.05, ortho_err=oe, workspace=ws)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        Rb = ktgen.to_f64(ktgen.bf16_round(R[b].cpu())) if dtype == "bf16" else ktgen.to_f64(R[b].cpu())
+        Xb = ktgen.to_f64(X[b].cpu().contiguous())
+        o = oracle.loss_grad(Xb, Rb)
+        assert abs(loss[b].item() - o["loss"]) <= tol * o["loss"]
+        assert np.max(np.abs(rk[b].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= tol
+        assert rel_fro(dR[b].cpu().numpy(), o["dR"]) <= tol
+        q = oracle.fakequant_int4(Xb, Rb, clip=0.95)
+        assert np.allclose(so[b].cpu().numpy(), q["scales"], rtol=1e-4)
+        diff = codes[b].cpu().numpy().astype(np.int32) - q["codes"].astype(np.int32)
+        assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 5e-3    # own scales: boundaries may move by rounding
+        assert np.allclose(err[b].cpu().numpy(), q["err"], rtol=5e-3)
+        ref = oracle.cayley_step(ktgen.to_f64(R[b].cpu()), dR[b].cpu().double().numpy(), 0.05)
+        stepn = np.linalg.norm(ref - ktgen.to_f64(R[b].cpu()))
+        assert np.linalg.norm(Rn[b].cpu().double().numpy() - ref) <= 1e-3 * stepn
+        assert oe[b].item() < 1e-6
