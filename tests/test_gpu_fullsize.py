@@ -298,19 +298,24 @@ def test_maximum_problem_count():
     dR = torch.empty((batch, d, d), device="cuda")
     rk = torch.empty((batch, n), device="cuda")
     loss = kt.kt_kurtosis_loss_grad(X, R, row_kurt=rk, dR=dR, workspace=ws)
-    Rn = R.clone()
-    oe = torch.zeros(batch, device="cuda")
-    info = torch.zeros(batch, dtype=torch.int32, device="cuda")
-    kt.kt_cayley_step(Rn, dR, lr, ortho_err=oe, info=info, workspace=ws)
     torch.cuda.synchronize()
-    assert float(oe.max()) < 1e-6 and int(info.min()) >= 1
-    for p in (0, 32767, batch - 1):
+    picked = (0, 32767, batch - 1)
+    G = torch.randn((batch, d, d), generator=torch.Generator(device="cuda").manual_seed(5), device="cuda") * 1e-3
+    for p in picked:
         Ro = ktgen.to_f64(ktgen.bf16_round(R[p]))
         o = oracle.loss_grad(ktgen.to_f64(X[p]), Ro)
         assert abs(loss[p].item() - o["loss"]) <= 2e-2 * o["loss"], p
         assert np.max(np.abs(rk[p].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= 2e-2, p
         assert rel_fro(dR[p].cpu().numpy(), o["dR"]) <= 2e-2, p
-        ref = oracle.cayley_step(ktgen.to_f64(R[p]), dR[p].cpu().double().numpy(), lr)
+        G[p] = torch.tensor(o["dR"], dtype=torch.float32).cuda()     # the oracle's gradient where it is checked
+    Rn = R.clone()
+    oe = torch.zeros(batch, device="cuda")
+    info = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    kt.kt_cayley_step(Rn, G, lr, ortho_err=oe, info=info, workspace=ws)
+    torch.cuda.synchronize()
+    assert float(oe.max()) < 1e-6 and int(info.min()) >= 1
+    for p in picked:
+        ref = oracle.cayley_step(ktgen.to_f64(R[p]), ktgen.to_f64(G[p]), lr)
         stepn = np.linalg.norm(ref - ktgen.to_f64(R[p]))
         assert np.linalg.norm(Rn[p].cpu().double().numpy() - ref) <= 1e-3 * stepn, p
     with pytest.raises(Exception):

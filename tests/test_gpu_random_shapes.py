@@ -44,10 +44,8 @@ def test_random_shape(dtype, d, n, batch, pad, seed):
     codes = torch.empty((batch, n, d), dtype=torch.int8, device="cuda")
     err = torch.empty((batch, n, 2), device="cuda")
     kt.kt_rotate_fakequant_int4(X, R, clip_ratio=0.95, scales_out=so, codes=codes, err=err, workspace=ws)
-    Rn = R.clone()
-    oe = torch.zeros(batch, device="cuda")
-    kt.kt_cayley_step(Rn, dR, 0.05, ortho_err=oe, workspace=ws)
     torch.cuda.synchronize()
+    ref_dR = []
     for b in range(batch):
         Rb = ktgen.to_f64(ktgen.bf16_round(R[b].cpu())) if dtype == "bf16" else ktgen.to_f64(R[b].cpu())
         Xb = ktgen.to_f64(X[b].cpu().contiguous())
@@ -60,7 +58,15 @@ def test_random_shape(dtype, d, n, batch, pad, seed):
         diff = codes[b].cpu().numpy().astype(np.int32) - q["codes"].astype(np.int32)
         assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 5e-3    # own scales: boundaries may move by rounding
         assert np.allclose(err[b].cpu().numpy(), q["err"], rtol=5e-3)
-        ref = oracle.cayley_step(ktgen.to_f64(R[b].cpu()), dR[b].cpu().double().numpy(), 0.05)
+        ref_dR.append(o["dR"])
+    # the retraction on the ORACLE's gradient (rounded to fp32), both sides from the same numbers
+    G = torch.tensor(np.stack(ref_dR), dtype=torch.float32)
+    Rn = R.clone()
+    oe = torch.zeros(batch, device="cuda")
+    kt.kt_cayley_step(Rn, G.cuda(), 0.05, ortho_err=oe, workspace=ws)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        ref = oracle.cayley_step(ktgen.to_f64(R[b].cpu()), ktgen.to_f64(G[b]), 0.05)
         stepn = np.linalg.norm(ref - ktgen.to_f64(R[b].cpu()))
         assert np.linalg.norm(Rn[b].cpu().double().numpy() - ref) <= 1e-3 * stepn
         assert oe[b].item() < 1e-6

@@ -45,10 +45,8 @@ def test_against_oracle(dist, count, bits):
 
 def test_on_rotated_activations_learned_rotation_lowers_the_error():
     X, R, cfg = ktgen.make_problem("C1", seed=0, n=1024)
-    def rotated(Rm):
-        Y = torch.empty((1, 1024, 256), device="cuda")
-        kt.kt_rotate_quant_metrics(X.cuda(), Rm.cuda(), quantile=1.0, Y=Y)
-        return Y.reshape(-1).cpu()
+    def rotated(Rm):   # input data for both sides: a plain fp32 product on the host
+        return (X[0].float() @ Rm[0].float()).reshape(-1)
     s0, mse0, _ = _check(rotated(torch.eye(256).unsqueeze(0)))
     s1, mse1, _ = _check(rotated(R))
     assert mse1 < mse0            # a rotation spreads the outlier channels: smaller tensor-wide int4 error
