@@ -232,3 +232,20 @@ def test_staged_path_with_row_stride_matches_the_contiguous_call():
     ref = oracle.fakequant_int4(ktgen.to_f64(Xc[1].cpu()), ktgen.to_f64(ktgen.bf16_round(R[1].cpu())), clip=0.9)
     assert np.allclose(outs[0][1][1].numpy(), ref["scales"], rtol=1e-5)
     assert (outs[0][0][1].numpy() != ref["codes"]).mean() < 2e-3
+
+def test_two_problems_each_longer_than_a_staging_slice_at_d_8192():
+    """d = 8192 (a row fills the row kernel's registers: 128 per lane), 33000 tokens per problem: every problem
+    needs a full slice of 32768 rows and a ragged one of its own."""
+    batch, n, d = 2, 33000, 8192
+    g = torch.Generator(device="cuda").manual_seed(13)
+    Rs = []
+    for b in range(batch):
+        q, r = torch.linalg.qr(torch.randn((d, d), generator=g, device="cuda"))
+        Rs.append((q * torch.sign(torch.diagonal(r)).unsqueeze(0)).contiguous())
+        del q, r
+    R = torch.stack(Rs)
+    del Rs
+    X = ktgen.make_x(batch * n, d, seed=23, outlier_cols=12, outlier_scale=40.0, t_frac=0.02, dtype="bf16",
+                     device="cuda").reshape(batch, n, d)
+    pick = {0: np.array([0, 32767, 32768, n - 1]), 1: np.array([0, 32767, 32768, 32900, n - 1])}
+    _check_picked(X, R, pick, _own_then_given(X, R, pick))
