@@ -70,3 +70,52 @@ def test_random_shape(dtype, d, n, batch, pad, seed):
         stepn = np.linalg.norm(ref - ktgen.to_f64(R[b].cpu()))
         assert np.linalg.norm(Rn[b].cpu().double().numpy() - ref) <= 1e-3 * stepn
         assert oe[b].item() < 1e-6
+
+
+def _variant_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        out.append((dtype, int(rng.choice([128, 256, 384, 512, 1024])), int(rng.integers(1, 2500)), int(rng.choice([1, 2, 3])),
+                    int(rng.choice([0, 8, 64])), bool(dtype == "bf16" and rng.random() < 0.5), float(rng.choice([0.0, 1.8, 3.0])),
+                    bool(rng.random() < 0.5), bool(rng.random() < 0.8), float(rng.choice([1.0, 0.9, 0.5])), int(rng.integers(0, 10000))))
+    return out
+
+
+@pytest.mark.parametrize("dtype,d,n,batch,rpad,r_bf16,target,want_rows,want_dR,clip,seed", _variant_cases(77, 10))
+def test_random_call_variant(dtype, d, n, batch, rpad, r_bf16, target, want_rows, want_dR, clip, seed):
+    """The ways a call can be made: R with a row stride and in bf16, a kurtosis target, outputs left out,
+    clipped scales, and the fake-quant with the oracle's scales handed in."""
+    X = torch.stack([ktgen.make_x(n, d, seed=seed + b, outlier_cols=3, outlier_scale=40.0, t_frac=0.03, dtype=dtype)
+                     for b in range(batch)]).cuda()
+    R32 = torch.stack([ktgen.random_orthogonal(d, seed=seed + 100 + b) for b in range(batch)])
+    Rbuf = torch.zeros((batch, d, d + rpad), dtype=torch.bfloat16 if r_bf16 else torch.float32, device="cuda")
+    Rbuf[:, :, :d] = R32.cuda().to(Rbuf.dtype)
+    R = Rbuf[:, :, :d]
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    ws = kt.Workspace()
+    rk = torch.empty((batch, n), device="cuda") if want_rows else None
+    dR = torch.empty((batch, d, d), device="cuda") if want_dR else None
+    loss = kt.kt_kurtosis_loss_grad(X, R, kappa_target=target, row_kurt=rk, dR=dR, workspace=ws)
+    torch.cuda.synchronize()
+    quant = []
+    for b in range(batch):
+        Rb = ktgen.to_f64(ktgen.bf16_round(R32[b])) if dtype == "bf16" else ktgen.to_f64(R32[b])
+        Xb = ktgen.to_f64(X[b].cpu())
+        o = oracle.loss_grad(Xb, Rb, kappa_target=target, want_dR=want_dR)
+        assert abs(loss[b].item() - o["loss"]) <= tol * o["loss"]
+        if want_rows:
+            assert np.max(np.abs(rk[b].cpu().numpy() - o["row_kurt"]) / o["row_kurt"]) <= tol
+        if want_dR:
+            assert rel_fro(dR[b].cpu().numpy(), o["dR"]) <= tol
+        quant.append(oracle.fakequant_int4(Xb, Rb, clip=clip))
+    sin = torch.tensor(np.stack([q["scales"] for q in quant]), dtype=torch.float32).cuda()
+    codes = torch.empty((batch, n, d), dtype=torch.int8, device="cuda")
+    so = torch.empty((batch, n), device="cuda")
+    kt.kt_rotate_fakequant_int4(X, R, clip_ratio=clip, scales_in=sin, scales_out=so, codes=codes, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(so, sin)
+    for b in range(batch):
+        diff = codes[b].cpu().numpy().astype(np.int32) - quant[b]["codes"].astype(np.int32)
+        assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-3
