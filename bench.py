@@ -30,6 +30,18 @@ MEASURED_TRAFFIC_BYTES = {"C3": {0: (6.00 + 0.0625) * 2**30, 1: (6.01 + 1.0) * 2
 CPU_SAMPLE_ROWS = {"C1": 2048, "C2": 32768, "C3": 16384, "C4": 131072, "C5": 4096}
 
 
+def gpu_state():
+    """Clocks and power as rocm-smi reports them right after the timed region (context for the roofline
+    fraction: the chip does not hold its peak clock under this load); None if the tool is not there."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=10)
+        card = next(iter(json.loads(r.stdout).values()))
+        return {k.strip(" :"): v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "power"))}
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,6 +167,7 @@ def main():
     marks[args.steps].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    state = gpu_state()
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
@@ -317,6 +330,7 @@ def main():
         "frac_of_bf16_peak_algorithmic": round(alg_tflops / peak, 4),
         "roofline": roofline, "kernels_ms": breakdown, "cpu_baseline": cpu,
         "loss_first_last": [float(loss_first[0]), float(loss[0])], "input_gen_s": round(gen_s, 1),
+        "gpu_state_after_timed_region": state,
         "context": "paper: SpinQuant needs >= 4x H100 80GB for Llama3-70B rotations, KurTail a single GPU",
     }
     print(json.dumps(out))
