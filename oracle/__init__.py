@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     fakequant_int4,
     quant_metrics,
     quant_sensitivity,
+    quant_mse,
     hadamard_rows,
     hadamard_factor,
     hadamard_matrix,

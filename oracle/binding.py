@@ -49,7 +49,7 @@ def _load():
     cd = ctypes.c_double
     lib.kto_cayley_adam_step.argtypes = [dp, dp, dp, cd, i64, i64, cd, cd, cd, cd, cd, dp, dp, dp, dp]
     lib.kto_cayley_adam_step.restype = ctypes.c_int
-    lib.kto_quant_metrics.argtypes = [dp, dp, fp, i64, i64, ctypes.c_double, fp, fp, dp, dp]
+    lib.kto_quant_metrics.argtypes = [dp, dp, i64, i64, ctypes.c_double, fp, fp, dp, dp]
     lib.kto_quant_metrics.restype = ctypes.c_int64
     lib.kto_hadamard_rows.argtypes = [dp, dp, i64, i64, dp]
     lib.kto_hadamard_rows.restype = ctypes.c_int
@@ -59,7 +59,9 @@ def _load():
     lib.kto_hadamard_matrix.restype = None
     lib.kto_fuse_rotation.argtypes = [dp, dp, i64, i64, ctypes.c_int, dp]
     lib.kto_fuse_rotation.restype = None
-    lib.kto_quant_sensitivity.argtypes = [fp, i64, ctypes.c_int, fp, ctypes.c_int, dp, dp]
+    lib.kto_quant_sensitivity.argtypes = [fp, i64, ctypes.c_int, fp, ctypes.c_int, ctypes.c_double, dp, dp]
+    lib.kto_quant_mse.argtypes = [fp, i64, ctypes.c_int, ctypes.c_float]
+    lib.kto_quant_mse.restype = ctypes.c_double
     lib.kto_quant_sensitivity.restype = None
     lib.kto_fakequant_int4.argtypes = [dp, dp, i64, i64, ctypes.c_float, fp, fp, i8p, dp]
     lib.kto_fakequant_int4.restype = None
@@ -181,20 +183,16 @@ def fakequant_int4(X, R, clip=1.0, scales_in=None):
     return {"scales": sout, "codes": codes, "err": err}
 
 
-def quant_metrics(X, R, quantile=0.98, Y=None):
-    """Per-token quantisation-quality figures.  Y (float32 [n][d]) replaces X R when given.
+def quant_metrics(X, R, quantile=0.98):
+    """Per-token quantisation-quality figures of Y = X R.
     Returns dict(success int, amax float32[n][2], thr float32[n], err_sym, err_asym float64[n][2])."""
     X, R = _d(X), _d(R)
     n, d = X.shape
-    Yf = None
-    if Y is not None:
-        Yf = np.ascontiguousarray(np.asarray(Y, dtype=np.float32))
-        assert Yf.shape == (n, d)
     amax = np.empty((n, 2), dtype=np.float32)
     thr = np.empty(n, dtype=np.float32)
     es = np.empty((n, 2), dtype=np.float64)
     ea = np.empty((n, 2), dtype=np.float64)
-    succ = _load().kto_quant_metrics(_p(X), _p(R), _p(Yf, ctypes.c_float), n, d, float(quantile),
+    succ = _load().kto_quant_metrics(_p(X), _p(R), n, d, float(quantile),
                                      _p(amax, ctypes.c_float), _p(thr, ctypes.c_float), _p(es), _p(ea))
     return {"success": int(succ), "amax": amax, "thr": thr, "err_sym": es, "err_asym": ea}
 
@@ -237,14 +235,21 @@ def fuse_rotation(W, R, side):
     return out
 
 
-def quant_sensitivity(y, alphas, bits=4):
-    """Optimal step of a symmetric `bits`-bit quantiser over all of y (float32) and the sensitivity
-    Gamma at the step fractions `alphas`.  Returns dict(s_opt, mse_opt, gamma float64[len(alphas)])."""
+def quant_mse(y, s, bits=4):
+    """Eq. 1: mean squared error of the symmetric `bits`-bit quantiser with step s over all of y."""
+    yf = np.ascontiguousarray(np.asarray(y, dtype=np.float32)).ravel()
+    return float(_load().kto_quant_mse(_p(yf, ctypes.c_float), yf.size, int(bits), float(np.float32(s))))
+
+
+def quant_sensitivity(y, alphas, bits=4, flat_tol=1e-3):
+    """Optimal step of a symmetric `bits`-bit quantiser over all of y (float32), by a dense scan and a
+    bracketed refinement, and the sensitivity Gamma at the step fractions `alphas`.
+    Returns dict(s_opt, mse_opt, flat (s_lo, s_hi): the steps around s_opt whose MSE stays within
+    (1 + flat_tol) of the minimum, gamma float64[len(alphas)])."""
     yf = np.ascontiguousarray(np.asarray(y, dtype=np.float32)).ravel()
     al = np.ascontiguousarray(np.asarray(alphas, dtype=np.float32))
-    out = np.empty(2, dtype=np.float64)
+    out = np.empty(4, dtype=np.float64)
     gam = np.empty(al.size, dtype=np.float64)
     _load().kto_quant_sensitivity(_p(yf, ctypes.c_float), yf.size, int(bits), _p(al, ctypes.c_float), al.size,
-                                  _p(out), _p(gam))
-    return {"s_opt": float(out[0]), "mse_opt": float(out[1]), "gamma": gam}
-
+                                  float(flat_tol), _p(out), _p(gam))
+    return {"s_opt": float(out[0]), "mse_opt": float(out[1]), "flat": (float(out[2]), float(out[3])), "gamma": gam}

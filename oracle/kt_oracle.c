@@ -526,8 +526,7 @@ static int cmp_float(const void *a, const void *b) {
 }
 
 /*
- * Per token row of Y = X R (or of Y_in, n*d floats, when given: the rotation is then skipped
- * and y = (double)Y_in), with yf = (float)y and every rounding-critical step in IEEE single:
+ * Per token row of Y = X R, with yf = (float)y and every rounding-critical step in IEEE single:
  *   amax[i]   = { max_j |x_ij| as float, max_j |yf_ij| };   success = amax_rot < amax_base
  *   symmetric int4, scale clipped at the quantile `quant` of |yf| over the row (linear
  *   interpolation between order statistics: pos = quant (d-1), k = floor(pos),
@@ -539,13 +538,10 @@ static int cmp_float(const void *a, const void *b) {
  * A row with s == 0 reproduces itself for asym (yhat = b) and gives yhat = 0 for sym.
  * Returns the number of successes.  Output pointers may be NULL.
  */
-int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, int64_t n, int64_t d,
+int64_t kto_quant_metrics(const double *X, const double *R, int64_t n, int64_t d,
                           double quant, float *amax, float *thr, double *err_sym, double *err_asym) {
-  double *Y = NULL;
-  if (!Y_in) {
-    Y = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
-    kto_rotate(X, R, n, d, Y);
-  }
+  double *Y = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
+  kto_rotate(X, R, n, d, Y);
   int64_t succ = 0;
 #pragma omp parallel for schedule(static) reduction(+ : succ)
   for (int64_t i = 0; i < n; ++i) {
@@ -553,7 +549,7 @@ int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, i
     float ab = 0.0f, ar = 0.0f, mn = 0.0f, mx = 0.0f;
     double y2 = 0.0;
     for (int64_t j = 0; j < d; ++j) {
-      const double yd = Y_in ? (double)Y_in[i * d + j] : Y[i * d + j];
+      const double yd = Y[i * d + j];
       const float yf = (float)yd;
       const float xa = fabsf((float)X[i * d + j]);
       if (xa > ab) ab = xa;
@@ -582,7 +578,7 @@ int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, i
     const float sa = span / 15.0f;
     double es = 0.0, ea = 0.0;
     for (int64_t j = 0; j < d; ++j) {
-      const double yd = Y_in ? (double)Y_in[i * d + j] : Y[i * d + j];
+      const double yd = Y[i * d + j];
       const float yf = (float)yd;
       double yh = 0.0;
       if (ss > 0.0f) {
@@ -610,7 +606,7 @@ int64_t kto_quant_metrics(const double *X, const double *R, const float *Y_in, i
     if (err_asym) { err_asym[2 * i] = ea; err_asym[2 * i + 1] = y2; }
     free(a);
   }
-  if (Y) free(Y);
+  free(Y);
   return succ;
 }
 
@@ -783,60 +779,65 @@ static double mse_at_step(const float *y, int64_t count, float s, int L) {
   return acc / (double)count;
 }
 
+/* Eq. 1 at one step, exported for the pins. */
+double kto_quant_mse(const float *y, int64_t count, int bits, float s) {
+  return mse_at_step(y, count, s, (1 << (bits - 1)) - 1);
+}
+
 /*
- * Optimal step by three stages of a 32-point grid, then Gamma at the given fractions.
- *   stage 0: s_j = smax c_j, smax = amax / L, c_j = 2^(-j/4), j = 0..31 (down to smax / 215)
- *   stages 1, 2: 32 points spread evenly between the neighbours of the best point so far
- *   (lo + (hi - lo) (j + 1) / 33 in fp32); the best of all points evaluated is s_opt.
- *   gamma[i] = | MSE(s_opt (1 + alpha_i)) - MSE(s_opt) |.
- * out[0] = s_opt, out[1] = MSE(s_opt).  Candidate steps are formed in fp32, one operation at a time.
+ * Quantisation sensitivity (Background: Definition "Quantization Sensitivity", Eq. 1), as the
+ * definition reads: s_opt = argmin_s MSE(s), Gamma(alpha) = | MSE(s_opt (1 + alpha)) - MSE(s_opt) |.
+ * The argmin is taken by a dense scan: KTO_SENS_GRID steps spaced evenly in log s from
+ * smax = max|y| / L (the largest step that still uses the outermost level; beyond it nothing is
+ * clipped and the error only grows) down to smax / 1024, then a golden-section search between the
+ * two grid neighbours of the best grid point; s_opt is the best step evaluated anywhere.
+ *   out[0] = s_opt, out[1] = MSE(s_opt),
+ *   out[2], out[3] = the ends of the run of consecutive grid steps around the best grid point
+ *                    whose MSE stays within (1 + flat_tol) MSE(s_opt): how flat the minimum is.
+ *   gamma[i] = | MSE(s_opt (1 + alphas[i])) - MSE(s_opt) |   (step formed in fp32).
  */
+#define KTO_SENS_GRID 4096
 void kto_quant_sensitivity(const float *y, int64_t count, int bits, const float *alphas, int n_alpha,
-                           double *out, double *gamma) {
-  static const float c4[4] = {1.0f, 0.840896415f, 0.707106781f, 0.594603558f}; /* 2^(-k/4) */
+                           double flat_tol, double *out, double *gamma) {
   const int L = (1 << (bits - 1)) - 1;
   float amax = 0.0f;
   for (int64_t i = 0; i < count; ++i) { const float a = fabsf(y[i]); if (a > amax) amax = a; }
-  const float smax = amax / (float)L;
-  float steps[32];
-  double mse[32];
-  float best_s = smax, lo = smax, hi = smax;
-  double best = -1.0;
-  for (int round = 0; round < 3; ++round) {
-    for (int j = 0; j < 32; ++j) {
-      if (round == 0) {
-        volatile float c = ldexpf(c4[j & 3], -(j >> 2));
-        steps[j] = smax * c;
-      } else {
-        volatile float span = hi - lo;
-        volatile float f = (float)(j + 1) / 33.0f;
-        volatile float inc = span * f;
-        steps[j] = lo + inc;
-      }
-      mse[j] = mse_at_step(y, count, steps[j], L);
-    }
-    int arg = 0;
-    for (int j = 1; j < 32; ++j) if (mse[j] < mse[arg]) arg = j;
-    float nlo, nhi;
-    if (round == 0) {            /* steps descend: neighbours j+1 (smaller) and j-1 (larger) */
-      nlo = steps[arg + 1 < 32 ? arg + 1 : arg];
-      nhi = steps[arg > 0 ? arg - 1 : arg];
-    } else {                     /* steps ascend inside (lo, hi) */
-      nlo = arg > 0 ? steps[arg - 1] : lo;
-      nhi = arg + 1 < 32 ? steps[arg + 1] : hi;
-    }
-    if (best < 0.0 || mse[arg] < best) { best = mse[arg]; best_s = steps[arg]; lo = nlo; hi = nhi; }
-    else { /* no better point in this round: shrink around the incumbent */
-      volatile float q1 = best_s - lo, q2 = hi - best_s;
-      lo = best_s - 0.25f * q1; hi = best_s + 0.25f * q2;
-    }
+  const double smax = (double)amax / (double)L;
+  double *mse = (double *)malloc(sizeof(double) * KTO_SENS_GRID);
+  float *grid = (float *)malloc(sizeof(float) * KTO_SENS_GRID);
+  int arg = 0;
+  for (int k = 0; k < KTO_SENS_GRID; ++k) {       /* descending: grid[0] = smax */
+    grid[k] = (float)(smax * exp(-log(1024.0) * (double)k / (double)(KTO_SENS_GRID - 1)));
+    mse[k] = mse_at_step(y, count, grid[k], L);
+    if (mse[k] < mse[arg]) arg = k;
   }
+  double best = mse[arg];
+  float best_s = grid[arg];
+  /* golden-section search on [a, b] = the two neighbours of the best grid point */
+  double a = (double)grid[arg + 1 < KTO_SENS_GRID ? arg + 1 : arg], b = (double)grid[arg > 0 ? arg - 1 : arg];
+  const double phi = 0.5 * (sqrt(5.0) - 1.0);
+  double x1 = b - phi * (b - a), x2 = a + phi * (b - a);
+  double f1 = mse_at_step(y, count, (float)x1, L), f2 = mse_at_step(y, count, (float)x2, L);
+  for (int it = 0; it < 48 && b > a; ++it) {
+    if (f1 < best) { best = f1; best_s = (float)x1; }
+    if (f2 < best) { best = f2; best_s = (float)x2; }
+    if (f1 <= f2) { b = x2; x2 = x1; f2 = f1; x1 = b - phi * (b - a); f1 = mse_at_step(y, count, (float)x1, L); }
+    else          { a = x1; x1 = x2; f1 = f2; x2 = a + phi * (b - a); f2 = mse_at_step(y, count, (float)x2, L); }
+  }
+  if (f1 < best) { best = f1; best_s = (float)x1; }
+  if (f2 < best) { best = f2; best_s = (float)x2; }
+  int lo = arg, hi = arg;                         /* grid descends: lo walks to smaller steps */
+  while (lo + 1 < KTO_SENS_GRID && mse[lo + 1] <= (1.0 + flat_tol) * best) ++lo;
+  while (hi > 0 && mse[hi - 1] <= (1.0 + flat_tol) * best) --hi;
   out[0] = (double)best_s;
   out[1] = best;
+  out[2] = (double)grid[lo];
+  out[3] = (double)grid[hi];
   for (int i = 0; i < n_alpha; ++i) {
     volatile float f = 1.0f + alphas[i];
     const float s = best_s * f;
     gamma[i] = fabs(mse_at_step(y, count, s, L) - best);
   }
+  free(mse);
+  free(grid);
 }
-

@@ -1,7 +1,10 @@
-"""GPU parity of kt_quant_sensitivity against the oracle, both on the same fp32 tensor and both
-following the same grid refinement.  MSE(s_opt) agrees to 1e-4; the optimal step to one cell of the
-last grid (near-ties between neighbouring candidates may resolve differently in fp32 sums), which
-moves Gamma by a few per cent at the fractions tested."""
+"""GPU parity of kt_quant_sensitivity against the oracle on the same fp32 tensor.  The oracle takes the
+Definition as it reads (Background, "Quantization Sensitivity", Eq. 1): a dense scan of MSE(s) plus a bracketed
+refinement for the argmin; the library searches its own way.  What must agree: the minimum it reports lies within
+1e-3 of the oracle's (and not below it by more than summation rounding), its step lies inside the stretch of steps
+whose MSE the oracle finds within 2e-3 of the minimum (the width of the flat bottom; the argmin itself is not
+unique to better than that), and Gamma agrees to 5 % + 1e-4 MSE_opt: it is evaluated at each side's own optimal
+step, and a shift of the step inside the flat bottom moves it by a few per cent at the fractions tested."""
 import numpy as np
 import pytest
 import torch
@@ -18,10 +21,11 @@ def _check(y, bits=4):
     yd = y.cuda().contiguous()
     out, gamma = kt.kt_quant_sensitivity(yd, torch.tensor(ALPHAS, device="cuda"), bits=bits)
     torch.cuda.synchronize()
-    o = oracle.quant_sensitivity(y.numpy(), ALPHAS, bits=bits)
+    o = oracle.quant_sensitivity(y.numpy(), ALPHAS, bits=bits, flat_tol=2e-3)
     s_gpu, mse_gpu = float(out[0]), float(out[1])
-    assert abs(mse_gpu - o["mse_opt"]) <= 1e-4 * o["mse_opt"]
-    assert abs(s_gpu - o["s_opt"]) <= 2e-3 * o["s_opt"]
+    assert -1e-4 * o["mse_opt"] <= mse_gpu - o["mse_opt"] <= 1e-3 * o["mse_opt"], (mse_gpu, o["mse_opt"])
+    lo, hi = o["flat"]
+    assert lo * (1 - 2e-3) <= s_gpu <= hi * (1 + 2e-3), (s_gpu, o["s_opt"], lo, hi)
     g = gamma.cpu().numpy()
     assert np.all(np.abs(g - o["gamma"]) <= 0.05 * o["gamma"] + 1e-4 * o["mse_opt"]), (g, o["gamma"])
     return s_gpu, mse_gpu, g

@@ -77,13 +77,3 @@ def test_success_counts_on_constructed_rotations():
     assert oracle.quant_metrics(X, np.eye(d), 1.0)["success"] == 0     # equal is not smaller
     Xf = np.ones((4, d))                          # flat rows: the Hadamard rotation concentrates them
     assert oracle.quant_metrics(Xf, H, 1.0)["success"] == 0
-
-
-def test_given_y_replaces_the_rotation():
-    rng = np.random.default_rng(5)
-    X, R = rng.standard_normal((9, 32)), np.linalg.qr(rng.standard_normal((32, 32)))[0]
-    Y32 = (X @ R).astype(np.float32)
-    a = oracle.quant_metrics(X, R, 0.98)
-    b = oracle.quant_metrics(X, R, 0.98, Y=Y32)
-    assert np.array_equal(a["thr"], b["thr"]) and a["success"] == b["success"]
-    assert np.allclose(a["err_sym"], b["err_sym"], rtol=1e-5) and np.allclose(a["err_asym"], b["err_asym"], rtol=1e-5)
