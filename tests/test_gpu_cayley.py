@@ -59,6 +59,45 @@ def test_large_d_three_term_bf16_path(d, lr, gscale):
     assert torch.equal(lowp, Rn.to(torch.bfloat16))
 
 
+def _spectral_norm(A, iters=60):
+    """Largest singular value by power iteration on A^T A (host, fp64)."""
+    v = np.random.default_rng(0).standard_normal(A.shape[0])
+    for _ in range(iters):
+        v = A.T @ (A @ v)
+        v /= np.linalg.norm(v)
+    return float(np.linalg.norm(A @ v))
+
+
+def test_d4096_headline_tiles_against_oracle():
+    """The retraction as the benchmark's configuration runs it (d = 4096: 256 x 256 tiles, three-term bf16
+    products), against the oracle's exact LU solve ("Optimization in the Orthogonal Space").  R is C3's rotation,
+    the gradient is the oracle's own dR on a 512-row chunk of C3's activations (rounded to fp32 for both
+    sides).  Two steps: lr = 1e-2 (converges in a few iterations) and a step sized so that
+    (lr/2) ||A||_2 = 0.4, which needs more than eight iterations and so runs the late, single-launch form of
+    an iteration as well."""
+    X, R, cfg = ktgen.make_problem("C3", seed=0, n=512)
+    d = cfg["d"]
+    assert d == 4096
+    Ro = ktgen.to_f64(R[0])
+    dRo = oracle.loss_grad(ktgen.to_f64(X[0]), ktgen.to_f64(ktgen.bf16_round(R[0])))["dR"]
+    G = torch.tensor(dRo, dtype=torch.float32).unsqueeze(0)
+    Go = ktgen.to_f64(G[0])
+    A = Go @ Ro.T
+    A = A - A.T
+    lr_big = 2 * 0.4 / _spectral_norm(A)
+    for lr, long_run in ((1e-2, False), (float(np.float32(lr_big)), True)):
+        Rn, lowp, oe, info = _run(R, G, lr)
+        ref = oracle.cayley_step(Ro, Go, lr)
+        rel = rel_fro(Rn[0].numpy().astype(np.float64) - Ro, ref - Ro)
+        assert rel <= 1e-4, (lr, rel)
+        RtR = Rn[0].double().T @ Rn[0].double()
+        assert float((RtR - torch.eye(d, dtype=torch.float64)).abs().max()) < 1e-6
+        assert oe[0] < 1e-6 and 1 <= info[0] <= 32
+        if long_run:
+            assert info[0] > 8, info
+        assert torch.equal(lowp, Rn.to(torch.bfloat16))
+
+
 def test_zero_step_and_radial_gradient():
     d = 128
     R = ktgen.random_orthogonal(d, seed=4).unsqueeze(0)

@@ -53,6 +53,29 @@ def test_single_step_against_oracle(d, batch, k, lr, gscale):
     assert torch.equal(lowp, Rn.to(torch.bfloat16))
 
 
+def test_d4096_headline_tiles_against_oracle():
+    """Cayley Adam on the tile path the benchmark's configuration takes (d = 4096: 256 x 256 tiles, three-term bf16
+    products for the momentum products and the fixed point), against the oracle's exact solve."""
+    d = 4096
+    g = torch.Generator().manual_seed(d)
+    R = ktgen.random_orthogonal(d, seed=2).unsqueeze(0)
+    G = torch.randn((1, d, d), generator=g) / np.sqrt(d)
+    M = 0.3 * torch.randn((1, d, d), generator=g) / np.sqrt(d)
+    v = torch.tensor([0.8])
+    k, lr = 3, 0.05
+    Rn, Mn, vn, lowp, oe, info, sc = _gpu_step(R, G, M, v, k, lr)
+    o = oracle.cayley_adam_step(ktgen.to_f64(R[0]), ktgen.to_f64(G[0]), ktgen.to_f64(M[0]), float(v[0]), k, F(lr), **HP)
+    assert abs(vn[0].item() - o["v"]) <= 1e-6 * o["v"]
+    for i, key in enumerate(("r", "alpha", "w_norm")):
+        assert abs(sc[0, i] - o[key]) <= 1e-5 * o[key], key
+    assert rel_fro(Rn[0].numpy().astype(np.float64) - ktgen.to_f64(R[0]), o["R"] - ktgen.to_f64(R[0])) <= 1e-4
+    assert rel_fro(Mn[0].numpy().astype(np.float64), o["M"]) <= 1e-4
+    RtR = Rn[0].double().T @ Rn[0].double()
+    assert float((RtR - torch.eye(d, dtype=torch.float64)).abs().max()) < 1e-6
+    assert oe[0] < 1e-6 and 1 <= info[0] <= 32
+    assert torch.equal(lowp, Rn.to(torch.bfloat16))
+
+
 def test_clamp_engages_for_a_huge_learning_rate():
     d = 128
     R = ktgen.random_orthogonal(d, seed=1).unsqueeze(0)
