@@ -244,7 +244,7 @@ def quant_mse(y, s, bits=4):
 def quant_sensitivity(y, alphas, bits=4, flat_tol=1e-3):
     """Optimal step of a symmetric `bits`-bit quantiser over all of y (float32), by a dense scan and a
     bracketed refinement, and the sensitivity Gamma at the step fractions `alphas`.
-    Returns dict(s_opt, mse_opt, flat (s_lo, s_hi): the steps around s_opt whose MSE stays within
+    Returns dict(s_opt, mse_opt, flat (s_lo, s_hi): the smallest and largest scanned step whose MSE is within
     (1 + flat_tol) of the minimum, gamma float64[len(alphas)])."""
     yf = np.ascontiguousarray(np.asarray(y, dtype=np.float32)).ravel()
     al = np.ascontiguousarray(np.asarray(alphas, dtype=np.float32))

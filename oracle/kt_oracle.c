@@ -792,8 +792,9 @@ double kto_quant_mse(const float *y, int64_t count, int bits, float s) {
  * clipped and the error only grows) down to smax / 1024, then a golden-section search between the
  * two grid neighbours of the best grid point; s_opt is the best step evaluated anywhere.
  *   out[0] = s_opt, out[1] = MSE(s_opt),
- *   out[2], out[3] = the ends of the run of consecutive grid steps around the best grid point
- *                    whose MSE stays within (1 + flat_tol) MSE(s_opt): how flat the minimum is.
+ *   out[2], out[3] = the smallest and the largest grid step whose MSE is within (1 + flat_tol) of
+ *                    MSE(s_opt): how far apart steps that are as good as the optimum lie (for a
+ *                    small sample MSE(s) is jagged and such steps need not be neighbours).
  *   gamma[i] = | MSE(s_opt (1 + alphas[i])) - MSE(s_opt) |   (step formed in fp32).
  */
 #define KTO_SENS_GRID 4096
@@ -826,9 +827,9 @@ void kto_quant_sensitivity(const float *y, int64_t count, int bits, const float 
   }
   if (f1 < best) { best = f1; best_s = (float)x1; }
   if (f2 < best) { best = f2; best_s = (float)x2; }
-  int lo = arg, hi = arg;                         /* grid descends: lo walks to smaller steps */
-  while (lo + 1 < KTO_SENS_GRID && mse[lo + 1] <= (1.0 + flat_tol) * best) ++lo;
-  while (hi > 0 && mse[hi - 1] <= (1.0 + flat_tol) * best) --hi;
+  int lo = arg, hi = arg;                         /* grid descends: lo is the smallest such step */
+  for (int k = 0; k < KTO_SENS_GRID; ++k)
+    if (mse[k] <= (1.0 + flat_tol) * best) { if (k > lo) lo = k; if (k < hi) hi = k; }
   out[0] = (double)best_s;
   out[1] = best;
   out[2] = (double)grid[lo];

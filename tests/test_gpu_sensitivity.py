@@ -1,9 +1,8 @@
 """GPU parity of kt_quant_sensitivity against the oracle on the same fp32 tensor.  The oracle takes the
 Definition as it reads (Background, "Quantization Sensitivity", Eq. 1): a dense scan of MSE(s) plus a bracketed
 refinement for the argmin; the library searches its own way.  What must agree: the minimum it reports lies within
-1e-3 of the oracle's (and not below it by more than summation rounding), its step lies inside the stretch of steps
-whose MSE the oracle finds within 2e-3 of the minimum (the width of the flat bottom; the argmin itself is not
-unique to better than that), and Gamma agrees to 5 % + 1e-4 MSE_opt: it is evaluated at each side's own optimal
+1e-3 of the oracle's (and not below it by more than summation rounding), its step lies between the smallest and the largest
+step whose MSE the oracle finds within 2e-3 of the minimum (the argmin itself is not unique to better than that), and Gamma agrees to 5 % + 1e-4 MSE_opt: it is evaluated at each side's own optimal
 step, and a shift of the step inside the flat bottom moves it by a few per cent at the fractions tested."""
 import numpy as np
 import pytest
