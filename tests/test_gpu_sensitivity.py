@@ -2,8 +2,12 @@
 Definition as it reads (Background, "Quantization Sensitivity", Eq. 1): a dense scan of MSE(s) plus a bracketed
 refinement for the argmin; the library searches its own way.  What must agree: the minimum it reports lies within
 1e-3 of the oracle's (and not below it by more than summation rounding), its step lies between the smallest and the largest
-step whose MSE the oracle finds within 2e-3 of the minimum (the argmin itself is not unique to better than that), and Gamma agrees to 5 % + 1e-4 MSE_opt: it is evaluated at each side's own optimal
-step, and a shift of the step inside the flat bottom moves it by a few per cent at the fractions tested."""
+step whose MSE the oracle finds within 2e-3 of the minimum (the argmin itself is not unique to better than that), and Gamma.  Gamma is evaluated at each side's own optimal step, so it is only defined up to what it does over
+the steps that are as good as the optimum: the test takes, with the oracle's plain MSE (Eq. 1), Gamma at the
+oracle's step and at 48 steps spread over that range, keeps those whose MSE is within 2e-3 of the minimum, and
+asks the library's Gamma to lie between the smallest and the largest of them, widened by 5 % + 1e-4 MSE_opt (for a
+large sample the range collapses to a few per cent around the oracle's own Gamma; for a sample of a few hundred
+values MSE(s) is jagged and equally good steps give Gammas a quarter apart)."""
 import numpy as np
 import pytest
 import torch
@@ -26,7 +30,15 @@ def _check(y, bits=4):
     lo, hi = o["flat"]
     assert lo * (1 - 2e-3) <= s_gpu <= hi * (1 + 2e-3), (s_gpu, o["s_opt"], lo, hi)
     g = gamma.cpu().numpy()
-    assert np.all(np.abs(g - o["gamma"]) <= 0.05 * o["gamma"] + 1e-4 * o["mse_opt"]), (g, o["gamma"])
+    yn = y.numpy()
+    gam = [o["gamma"]]
+    for s in np.linspace(lo, hi, 48):
+        m = oracle.quant_mse(yn, s, bits=bits)
+        if m <= (1 + 2e-3) * o["mse_opt"]:
+            gam.append([abs(oracle.quant_mse(yn, np.float32(s) * (np.float32(1) + np.float32(a)), bits=bits) - m) for a in ALPHAS])
+    gam = np.array(gam)
+    slack = 1e-4 * o["mse_opt"]
+    assert np.all(g >= 0.95 * gam.min(0) - slack) and np.all(g <= 1.05 * gam.max(0) + slack), (g, gam.min(0), gam.max(0))
     return s_gpu, mse_gpu, g
 
 
