@@ -61,6 +61,11 @@ typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
 
+/* Identifier of the source files this binary was compiled from (set by the build script; the Python
+ * binding compares it with the sources it sees and rebuilds a library that no longer matches).
+ * Static storage.  Host call. */
+const char* kt_build_id(void);
+
 /* Text of the last error raised on the calling host thread ("" if none).
  * Points to thread-local static storage; never free it. */
 const char* kt_last_error(void);
@@ -135,11 +140,14 @@ kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R
  *   R+ = (I + lr/2 A)^-1 (I - lr/2 A) R
  *
  * The solve is the fixed-point iteration Z <- R - (lr/2) A (R + Z), run on the
- * device until successive iterates agree to the resolution of the arithmetic (max |dZ|
- * <= 3e-7; or <= 2e-5 and no longer shrinking; or, the iteration being linear, as soon as
- * the observed contraction rho = |dZ_k| / |dZ_k-1| < 1/4 bounds the distance to the fixed
- * point, 4 |dZ_k| rho, by 3e-7); it contracts when (lr/2)||A||_2 < 1 and
- * the library enqueues at most 32 iterations (enough up to about 0.6).  No learning-rate
+ * device until the iterate is within the resolution of the arithmetic of its limit.  The
+ * iteration is linear, so the changes d_k = max |Z_k - Z_k-1| shrink geometrically with a ratio
+ * rho that is estimated from them (over two steps, d_k / d_k-2 = rho^2, once three are there: the
+ * even and odd terms of the series can have different patterns), and the iterate is accepted
+ * when four times the bound d_k rho / (1 - rho) on its distance to the limit is below 3e-7, or
+ * when the changes are small (<= 2e-5) and have stopped shrinking (the rounding floor).  It
+ * contracts when (lr/2)||A||_2 < 1 and the library enqueues at most 32 iterations (enough up to
+ * about 0.55).  No learning-rate
  * clamp is applied: the caller chooses lr.  For d >= 1024 the d^3 products run on the
  * bf16 matrix cores as three-term bf16 products (about 2^-17 relative per term).
  *

@@ -14,7 +14,7 @@ KT_OP_FUSE_ROTATION, KT_OP_SENSITIVITY = 5, 6
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
            "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_fuse_rotation", "kt_quant_sensitivity", "kt_profile_enable", "kt_profile_read",
-           "kt_profile_reset")
+           "kt_profile_reset", "kt_build_id")
 
 
 class KtError(RuntimeError):
@@ -28,14 +28,33 @@ def lib_path():
 
 
 def lib():
-    """Load the library; built on first use only if no built library is present."""
+    """Load the library.  It is built first when no built library is present, and rebuilt when the one present
+    was compiled from other sources than those in csrc/ now (it carries an id of its sources): a stale library
+    is never loaded silently."""
     global _lib
     if _lib is not None:
         return _lib
+    from .build import build_library, source_id
     if not os.path.exists(_LIB_PATH):
-        from .build import build_library
         build_library()
     L = ctypes.CDLL(_LIB_PATH)
+    want = source_id()
+    try:
+        L.kt_build_id.restype = ctypes.c_char_p
+        have = L.kt_build_id().decode()
+    except AttributeError:
+        have = "(none)"
+    if have != want:
+        import warnings
+        warnings.warn(f"libkurtail.so was built from other sources (id {have}, csrc/ now {want}): rebuilding")
+        tmp = _LIB_PATH + ".stale"
+        os.replace(_LIB_PATH, tmp)     # the mapped file stays valid; the new one gets a fresh inode
+        build_library()
+        os.remove(tmp)
+        L = ctypes.CDLL(_LIB_PATH)
+        L.kt_build_id.restype = ctypes.c_char_p
+        if L.kt_build_id().decode() != want:
+            raise RuntimeError("libkurtail.so does not match its sources after a rebuild")
     vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     i32 = ctypes.c_int32
     L.kt_version.restype = i32

@@ -821,6 +821,11 @@ extern "C" {
 
 int32_t kt_version(void) { return 100; }
 
+#ifndef KT_BUILD_ID
+#define KT_BUILD_ID "unknown"
+#endif
+const char* kt_build_id(void) { return KT_BUILD_ID; }
+
 const char* kt_last_error(void) { return g_err; }
 
 size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype) {

@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
 
   // fixed point in transposed space: Zt <- Rt - U B^T, U <- Rt + Zt
   int used = -1;
-  float dprev = 0.f;
+  float dprev = 0.f, dprev2 = 0.f;
   for (int it = 0; it < max_iters; ++it) {
     c128_gemm_nt(bufA, bufB, acc, wm, wn2, l32, half);
     unsigned dmax = 0u;
@@ -220,7 +220,8 @@ __global__ __launch_bounds__(256) void cayley_d128_kernel(float* __restrict__ R,
         }
     dmax = c128_block_umax(dmax, red, wave, lane);  // its barrier also ends every wave's reads of bufA
     const float d1 = __uint_as_float(dmax);
-    const bool conv = cayley_converged_pair(d1, dprev, it > 0, tol);  // same rule as the generic path
+    const bool conv = cayley_converged_hist(d1, dprev, dprev2, it > 1 ? 2 : it, tol);  // same rule as the generic path
+    dprev2 = dprev;
     dprev = d1;
     if (conv) {
       used = it + 1;

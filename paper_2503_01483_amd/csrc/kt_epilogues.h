@@ -183,26 +183,33 @@ __device__ __forceinline__ unsigned wave_umax(unsigned v) {
 // delta[it] = max |Zt_new - Zt_old| (bit pattern of a non-negative float, max is
 // order independent so the result is deterministic).  The launch for iteration `it`
 // returns at once when iteration it-1 already met the tolerance.
-// Iteration k counts as converged when its delta is below the tolerance, or when it is
-// small (within 64 tolerances) and has stopped shrinking (>= 0.9 of the previous one):
-// the iterate then sits on the rounding floor of the arithmetic, which for the three-term
-// bf16 products lies at a few 1e-7 and would never pass a fixed fp32-sized tolerance.
-// One rule for every path: d1 = delta of iteration k, d0 = delta of iteration k-1.
-//  - below the tolerance; or
-//  - the iteration is linear and contracts geometrically, so after a step that shrank the change by
-//    rho = d1/d0 < 1/4 the iterate just written is within d1 rho/(1 - rho) of the fixed point: accept
-//    it when four times that bound is below the tolerance (saves the product that would only
-//    confirm it); or
-//  - small (within 64 tolerances) and no longer shrinking: the rounding floor of the arithmetic.
-__device__ __forceinline__ bool cayley_converged_pair(float d1, float d0, bool have_prev, float tol) {
-  if (d1 <= tol) return true;
-  if (!have_prev) return false;
-  if (d1 < 0.25f * d0 && 4.f * d1 * (d1 / d0) <= tol) return true;
-  if (!(d1 <= 64.f * tol)) return false;
-  return d1 >= 0.9f * d0;
+// When an iteration counts as converged.  The map is linear, Z_k+1 - Z_k = -B (Z_k - Z_k-1), so the
+// changes shrink geometrically with the spectral radius rho of B = (lr/2) A and the iterate just written
+// is within d_k rho / (1 - rho) of the fixed point (d_k = max |Z_k - Z_k-1|).  rho is estimated from the
+// changes themselves.  Even and odd powers of a skew matrix have different patterns (for a low-rank
+// gradient, B^2k is concentrated on a few entries and B^2k+1 is not, or the other way round), so that
+// successive maxima alternate between two levels: the ratio over TWO steps, d_k / d_k-2 = rho^2, does not
+// see that and is used as soon as three changes are there; with two, the one-step ratio.
+//  - first iteration: converged only if the whole step is below the tolerance;
+//  - 4 d_k rho / (1 - rho) <= tol (four times the distance bound), rho < 0.95; for rho < 0.2 this
+//    accepts an iterate before its own change is below the tolerance and saves the product that would only
+//    confirm it, for slow contractions it asks for more than d_k <= tol: what is left of the series then
+//    still matters for max |R^T R - I|;
+//  - the rounding floor: the change is small (within 64 tolerances) and has stopped shrinking over both of
+//    the last two steps (for the three-term bf16 products the floor lies at a few 1e-7 and would never pass
+//    a fixed fp32-sized tolerance).
+// d1, d0, d00: changes of iterations k, k-1, k-2; nprev: how many of d0, d00 exist (0, 1 or 2).
+__device__ __forceinline__ bool cayley_converged_hist(float d1, float d0, float d00, int nprev, float tol) {
+  if (nprev == 0) return d1 <= tol;
+  if (d1 == 0.f) return true;
+  const float rho = nprev >= 2 ? sqrtf(d1 / d00) : d1 / d0;
+  if (rho < 0.95f && 4.f * d1 * rho <= tol * (1.f - rho)) return true;
+  if (nprev < 2 || !(d1 <= 64.f * tol)) return false;
+  return d1 >= 0.9f * d0 && d1 >= 0.8f * d00;
 }
 __device__ __forceinline__ bool cayley_converged(const unsigned* dl, int k, float tol) {
-  return cayley_converged_pair(__uint_as_float(dl[k]), k > 0 ? __uint_as_float(dl[k - 1]) : 0.f, k > 0, tol);
+  return cayley_converged_hist(__uint_as_float(dl[k]), k > 0 ? __uint_as_float(dl[k - 1]) : 0.f,
+                               k > 1 ? __uint_as_float(dl[k - 2]) : 0.f, k > 1 ? 2 : k, tol);
 }
 
 // Unew is written as fp32, or (Usplit != null) as the [hi | hi | lo] bf16 operand of the
