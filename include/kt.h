@@ -165,6 +165,24 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * kt_cayley_step for callers that cannot allocate device memory and hold no workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks,
+ * kernels and results as kt_cayley_step, but the scratch is a static device array inside the library
+ * image (8 MiB per GPU the library runs on, held until the process ends); the call allocates and frees
+ * nothing (its address is looked up with hipGetSymbolAddress once per device, at the first call with
+ * that device current).
+ *  Limit: kt_workspace_bytes(KT_OP_CAYLEY, batch, 0, d, KT_F32) <= 8 MiB, i.e. d = 512 with batch 1,
+ *  d = 384 with batch <= 2, d = 256 with batch <= 6, d = 128 with batch <= 25; anything larger returns
+ *  KT_ERR_NOT_SUPPORTED before anything is enqueued.
+ *  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *  streams, different host threads) race and must be serialised by the caller.  The array keeps the
+ *  previous call's contents; every counter the kernels need at zero is cleared by a fill kernel at the
+ *  start of each call.
+ */
+kt_status kt_cayley_step_static(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d,
+                                float lr, float* ortho_err, int32_t* info, void* stream);
+
+/*
  * One Cayley Adam step on the orthogonal group: the optimiser the paper uses for all
  * rotations ("Learning the Rotations"; Setup).  The paper prints no formula and defers to
  * the cited work on optimisation over the Stiefel manifold; the step implemented here is

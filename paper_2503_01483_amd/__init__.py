@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     kt_kurtosis_loss_grad,
     kt_pooled_kurtosis_loss_grad,
     kt_cayley_step,
+    kt_cayley_step_static,
     kt_cayley_adam_step,
     kt_rotate_fakequant_int4,
     kt_rotate_quant_metrics,

@@ -14,7 +14,7 @@ KT_OP_FUSE_ROTATION, KT_OP_SENSITIVITY = 5, 6
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
            "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_fuse_rotation", "kt_quant_sensitivity", "kt_profile_enable", "kt_profile_read",
-           "kt_profile_reset", "kt_build_id")
+           "kt_profile_reset", "kt_cayley_step_static", "kt_build_id")
 
 
 class KtError(RuntimeError):
@@ -80,6 +80,8 @@ def lib():
     L.kt_quant_sensitivity.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, sz, vp]
     L.kt_cayley_step.restype = i32
     L.kt_cayley_step.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, sz, vp]
+    L.kt_cayley_step_static.restype = i32
+    L.kt_cayley_step_static.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp]
     L.kt_cayley_adam_step.restype = i32
     L.kt_cayley_adam_step.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, f32, f32, f32, f32, f32, vp, vp, vp,
                                       vp, sz, vp]
@@ -197,6 +199,17 @@ def kt_cayley_step(R, dR, lr, *, R_lowp=None, ortho_err=None, info=None, workspa
     ws = (workspace or Workspace(R.device)).get(need)
     _check(lib().kt_cayley_step(_ptr(Rv), _ptr(dR), _ptr(R_lowp), batch, d, float(lr), _ptr(ortho_err),
                                 _ptr(info), _ptr(ws), ws.numel(), _stream(stream)))
+    return R
+
+
+def kt_cayley_step_static(R, dR, lr, *, R_lowp=None, ortho_err=None, info=None, stream=None):
+    """kt_cayley_step on the library's own static device scratch: no workspace, no allocation (small sizes)."""
+    Rv = R if R.dim() == 3 else R.unsqueeze(0)
+    batch, d, _ = Rv.shape
+    assert Rv.is_contiguous() and dR.is_contiguous() and dR.numel() == Rv.numel()
+    assert R.dtype == torch.float32 and dR.dtype == torch.float32
+    _check(lib().kt_cayley_step_static(_ptr(Rv), _ptr(dR), _ptr(R_lowp), batch, d, float(lr), _ptr(ortho_err),
+                                       _ptr(info), _stream(stream)))
     return R
 
 

@@ -49,6 +49,39 @@ static bool ensure_dynamic_lds(const void* kernel, size_t bytes) {
   return true;
 }
 
+// ------------------------------------------------------------------ static scratch
+// Device memory owned by the library image itself, for the one entry point that must not allocate
+// (kt_cayley_step_static).  Every GPU the library runs on holds its own copy of the array at its own
+// address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the address a kernel can use is looked up once per device, with that device
+// current, and kept in g_scratch_ptr; nothing else in this file may pass `scratch` itself anywhere.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mu;
+
+// Address of this device's copy of the scratch array (null on failure; text in kt_last_error()).
+static void* static_scratch_of_current_device() {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) {
+    fail(KT_ERR_DEVICE, "no current HIP device (or device index beyond %d)", kMaxDevices - 1);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t rc = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (rc != hipSuccess || !ptr) {
+      fail(KT_ERR_DEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", device, hipGetErrorString(rc));
+      return nullptr;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  return g_scratch_ptr[device];
+}
+
 // ------------------------------------------------------------------ profiling -----
 // Optional event brackets around the large launches (see kt_profile_enable).
 struct ProfRecord { hipEvent_t start, stop; int id; };
@@ -935,6 +968,26 @@ kt_status kt_cayley_step(float* R, const float* dR, void* R_lowp, int64_t batch,
   if (d == 128)  // whole retraction of a problem inside one workgroup (kt_cayley_d128.h)
     return launch_cayley_d128<false>(R, dR, R_lowp, batch, 0.5f * lr, ortho_err, info, C128Adam{}, st);
   return cayley_run(p, ws, R, dR, R_lowp, batch, d, 0.5f * lr, nullptr, ortho_err, info, st);
+}
+
+kt_status kt_cayley_step_static(float* R, const float* dR, void* R_lowp, int64_t batch, int64_t d, float lr,
+                                float* ortho_err, int32_t* info, void* stream) {
+  g_err[0] = 0;
+  if (!R || !dR) return fail(KT_ERR_INVALID_ARG, "R and dR must not be null");
+  if (batch < 1 || d < 1) return fail(KT_ERR_INVALID_ARG, "batch and d must be positive");
+  if (d % 128 != 0) return fail(KT_ERR_BAD_SHAPE, "d = %lld is not a multiple of 128", (long long)d);
+  if (d > 16384 || batch > 65535) return fail(KT_ERR_BAD_SHAPE, "size out of range (d <= 16384, batch <= 65535)");
+  if (!(lr == lr) || lr - lr != 0.f) return fail(KT_ERR_INVALID_ARG, "lr must be finite");
+  const size_t need = plan_cayley(batch, d).total;
+  if (need > kStaticScratchBytes)
+    return fail(KT_ERR_NOT_SUPPORTED,
+                "batch = %lld, d = %lld needs %zu bytes of scratch; the library's static scratch holds %zu "
+                "(use kt_cayley_step with a workspace)", (long long)batch, (long long)d, need, kStaticScratchBytes);
+  void* ws = static_scratch_of_current_device();
+  if (!ws) return KT_ERR_DEVICE;
+  // same checks, plan and launches as the workspace form; the fixed point clears its own counters
+  // with a fill kernel, so whatever the previous call left in the array does not matter
+  return kt_cayley_step(R, dR, R_lowp, batch, d, lr, ortho_err, info, ws, kStaticScratchBytes, stream);
 }
 
 kt_status kt_cayley_adam_step(float* R, const float* dR, float* M, float* v, int64_t step, void* R_lowp,

@@ -149,3 +149,14 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "ONE GPU" in r.stderr
+
+
+def test_static_scratch_entry_rejects_what_does_not_fit_before_touching_a_device():
+    L = kt.lib()
+    fake = ctypes.c_void_p(4096)
+    assert L.kt_cayley_step_static(fake, fake, None, 2, 512, 0.01, None, None, None) == 6
+    assert "static scratch" in kt.kt_last_error()
+    assert L.kt_cayley_step_static(fake, fake, None, 1, 1024, 0.01, None, None, None) == 6
+    assert L.kt_cayley_step_static(None, fake, None, 1, 256, 0.01, None, None, None) == 1
+    assert L.kt_cayley_step_static(fake, fake, None, 1, 200, 0.01, None, None, None) == 2
+    assert L.kt_cayley_step_static(fake, fake, None, 1, 256, float("nan"), None, None, None) == 1
