@@ -30,16 +30,56 @@ MEASURED_TRAFFIC_BYTES = {"C3": {0: (6.00 + 0.0625) * 2**30, 1: (6.01 + 1.0) * 2
 CPU_SAMPLE_ROWS = {"C1": 2048, "C2": 32768, "C3": 16384, "C4": 131072, "C5": 4096}
 
 
-def gpu_state():
-    """Clocks and power as rocm-smi reports them right after the timed region (context for the roofline
-    fraction: the chip does not hold its peak clock under this load); None if the tool is not there."""
-    import subprocess
-    try:
-        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=10)
-        card = next(iter(json.loads(r.stdout).values()))
-        return {k.strip(" :"): v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "power"))}
-    except Exception:
-        return None
+class ClockSampler:
+    """Shader clock and board power WHILE the timed steps run: a host thread reads the driver's sysfs files
+    (pp_dpm_sclk: the level marked '*' is the current clock; hwmon power1_input, microwatts) every couple of
+    milliseconds between start() and stop().  The roofline peak is quoted at 2.4 GHz; this says what clock the
+    chip actually held under the load.  Returns None where the files are not readable."""
+
+    def __init__(self):
+        import glob
+        self.sclk = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))), None)
+        self.power = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))), None)
+        self.samples, self._stop, self._thread = [], False, None
+
+    def _read(self):
+        mhz = watts = None
+        try:
+            with open(self.sclk) as f:
+                for line in f:
+                    if "*" in line:
+                        mhz = float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+            with open(self.power) as f:
+                watts = float(f.read()) / 1e6
+        except Exception:
+            pass
+        return mhz, watts
+
+    def _run(self):
+        while not self._stop:
+            self.samples.append(self._read())
+            time.sleep(0.002)
+
+    def start(self):
+        if self.sclk is None or self.power is None:
+            return
+        import threading
+        self._thread = threading.Thread(target=self._run, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        if self._thread is None:
+            return None
+        self._stop = True
+        self._thread.join()
+        mhz = sorted(m for m, _ in self.samples if m is not None)
+        w = sorted(p for _, p in self.samples if p is not None)
+        if not mhz or not w:
+            return None
+        mid = lambda v: v[len(v) // 2]
+        return {"samples": len(self.samples), "sclk_mhz_median": mid(mhz), "sclk_mhz_min": mhz[0], "sclk_mhz_max": mhz[-1],
+                "power_w_median": round(mid(w), 1), "power_w_max": round(w[-1], 1),
+                "source": "sysfs pp_dpm_sclk / hwmon power1_input polled by a host thread during the timed steps"}
 
 
 def main():
@@ -160,6 +200,8 @@ def main():
     kt.kt_profile_reset()
     torch.cuda.synchronize()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    sampler = ClockSampler()
+    sampler.start()
     t0 = time.perf_counter()
     for i in range(args.steps):
         marks[i].record()
@@ -167,7 +209,7 @@ def main():
     marks[args.steps].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    state = gpu_state()
+    state = sampler.stop()
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = {k: kt.kt_profile_read(k) for k in range(6)}
     kt.kt_profile_enable(0)
@@ -283,13 +325,18 @@ def main():
                     "achieved": round(kern[dom]["tflops"], 2), "peak": peak, "unit": "TFLOP/s",
                     "frac": round(kern[dom]["tflops"] / peak, 4), "avg_launch_ms": round(kern[dom]["avg_ms"], 4),
                     "flops_per_launch": flops_launch,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dom) if args.n is None else None}
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get(dom) if args.n is None else None,
+                    "traffic_source": "carried from profiles/c3_gemm_counters.md (rocprofv3 --pmc runs of this command); "
+                                      "not measured in this run"}
     names = {0: "fused_pass_ms" if fused else "fwd_moments_ms", 1: "bwd_recompute_ms", 2: "grad_xtg_ms"}
     breakdown = {names[k]: round(kern[k]["avg_ms"], 4) for k in kern}
     if prof[3][1]:
         breakdown["x_transpose_ms"] = round(prof[3][0] / prof[3][1], 4)
     breakdown["cayley_ms"] = round(prof[4][0] / max(prof[4][1], 1), 4)
-    breakdown["cayley_iters_last"] = info.cpu().tolist()[:4]
+    iters = info.cpu().tolist()
+    breakdown["cayley_iters_last"] = iters[:4]
+    # a retraction that did not converge is rejected by the library (R unchanged): such a run did not do the step
+    cayley_ok = args.no_cayley or all(i > 0 for i in iters)
     alg_tflops = 4.0 * batch * n * d * d * args.steps / elapsed / 1e12
     hw_tflops = 6.0 * batch * n * d * d * args.steps / elapsed / 1e12
 
@@ -303,10 +350,25 @@ def main():
         t0 = time.perf_counter()
         o = oracle.loss_grad(Xs, Rs)
         cpu_s = time.perf_counter() - t0
-        cpu = {"value": round(rows / cpu_s, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+        # the oracle's Cayley step (fp64 LU) on its own gradient: at the config's d up to 2048, above that timed at
+        # d = 2048 on the leading block of R and dR and scaled by (d/2048)^3 (every part of it is cubic in d)
+        dc = min(d, 2048)
+        Rc = np.ascontiguousarray(ktgen.to_f64(R[0])[:dc, :dc])
+        Gc = np.ascontiguousarray(o["dR"][:dc, :dc])
+        t0 = time.perf_counter()
+        oracle.cayley_step(Rc, Gc, lr)
+        cay_meas = time.perf_counter() - t0
+        cay_s = cay_meas * (d / dc) ** 3
+        lg_rate = rows / cpu_s
+        step_rate = n / (n / lg_rate + (0.0 if args.no_cayley else cay_s))
+        cpu = {"value": round(step_rate, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle",
-               "sample": f"plain fp64 oracle loss+grad on the first {rows} token rows of problem 0 at d={d} "
-                         f"({cpu_s:.1f} s); Cayley step not included; not a tuned CPU baseline"}
+               "sample": f"plain fp64 oracle, one problem of the same workload: loss+grad on the first {rows} token rows "
+                         f"at d={d} ({cpu_s:.1f} s, {lg_rate:.1f} tokens/s, linear in rows) + its Cayley step (LU) "
+                         + (f"timed at d={dc} ({cay_meas:.1f} s) and scaled by (d/{dc})^3 to {cay_s:.1f} s"
+                            if dc != d else f"at d={d} ({cay_s:.2f} s)")
+                         + f"; value = n / (n / loss+grad rate + Cayley time) for n={n}; not a tuned CPU baseline",
+               "loss_grad_tokens_per_s": round(lg_rate, 2), "cayley_step_s": round(cay_s, 2)}
         # while the oracle result is here: the same rows through the GPU path must agree
         l2 = torch.zeros(1, device=dev)
         d2 = torch.empty((1, d, d), device=dev)
@@ -328,12 +390,21 @@ def main():
         "tflops_algorithmic_4nd2": round(alg_tflops, 2),
         "tflops_hardware_6nd2": None if fused else round(hw_tflops, 2),
         "frac_of_bf16_peak_algorithmic": round(alg_tflops / peak, 4),
+        "frac_of_bf16_peak_hardware": None if fused else round(hw_tflops / peak, 4),
+        # the stated goal is the WHOLE step at >= 50 % of the matrix peak; roofline.frac below is one launch
+        "step_target": {"frac_goal": 0.5, "met_algorithmic_4nd2": bool(alg_tflops / peak >= 0.5),
+                        "met_hardware_6nd2": None if fused else bool(hw_tflops / peak >= 0.5)},
         "roofline": roofline, "kernels_ms": breakdown, "cpu_baseline": cpu,
         "loss_first_last": [float(loss_first[0]), float(loss[0])], "input_gen_s": round(gen_s, 1),
-        "gpu_state_after_timed_region": state,
+        "gpu_state_during_timed_region": state,
         "context": "paper: SpinQuant needs >= 4x H100 80GB for Llama3-70B rotations, KurTail a single GPU",
     }
+    if not cayley_ok:
+        out["value"] = None
+        out["invalid"] = f"the Cayley fixed point did not converge (info = {iters[:4]}): the steps timed did not update R"
     print(json.dumps(out))
+    if not cayley_ok:
+        sys.exit(3)
 
 
 if __name__ == "__main__":

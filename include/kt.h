@@ -100,8 +100,9 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
  *  loss     [batch] fp32, written.
  *  row_kurt [batch][n] fp32 or NULL.
  *  dR       [batch][d][d] fp32 or NULL (NULL: loss only, the backward GEMMs are skipped).
- *  A row without spread (m2 <= 1e-5 of its mean square, fp32 resolution) counts with
- *  kappa = 0 and contributes no gradient.
+ *  A row without spread (m2 <= 1e-10 of its mean square: sigma below 1e-5 of the mean, which fp32
+ *  products cannot resolve) counts with kappa = 0 and contributes no gradient.  Above that the row
+ *  values carry an error of about 1e-6 |mean| / sigma on top of the path tolerance.
  */
 kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
                                 int64_t batch, int64_t n, int64_t d,

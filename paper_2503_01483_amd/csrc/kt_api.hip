@@ -125,6 +125,10 @@ constexpr int kCayleyMaxIters = 32;
 constexpr float kCayleyTol = 3e-7f;
 constexpr int kCayleyFusedFrom = 6;  // three-term path: iterations from here on are single launches
 
+#ifdef KT_PHASE_STAMPS
+static int g_stamp_next = -1;  // developer build: slot the next GEMM launch records its phase stamps in (-1: none)
+#endif
+
 template <class TL, class Epi, bool ATN = false>
 static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const void* B, int64_t ldb,
                         int64_t bsb, int N, int64_t K, int slabs_per_split, int batch,
@@ -156,6 +160,9 @@ static bool launch_gemm(const void* A, int64_t lda, int64_t bsa, int M, const vo
   g.block_bytes_a = block_stride_a * (int64_t)sizeof(typename TL::T);
   g.block_bytes_b = block_stride_b * (int64_t)sizeof(typename TL::T);
   g.k_valid = k_valid;
+#ifdef KT_PHASE_STAMPS
+  g.stamp_slot = g_stamp_next >= 0 && g_stamp_next < kStampSlots ? g_stamp_next++ : -1;
+#endif
   hipLaunchKernelGGL(kern, dim3(g.grid_padded, batch), dim3(TL::NT), lds_bytes, stream, g, epi);
   return launch_ok();
 }
@@ -1228,6 +1235,18 @@ kt_status kt_quant_sensitivity(const float* Y, int64_t count, int32_t bits, cons
   }
   return KT_OK;
 }
+
+#ifdef KT_PHASE_STAMPS
+// Developer build only: arm the phase stamps (the next kStampSlots GEMM launches record into slots 0, 1, ...) and
+// read them back (synchronises the device).
+void kt_debug_stamps_arm(void) { g_stamp_next = 0; }
+int kt_debug_stamps_read(void* host_dst, size_t bytes) {
+  g_stamp_next = -1;
+  if (hipDeviceSynchronize() != hipSuccess) return -1;
+  const size_t all = sizeof(unsigned long long) * kStampSlots * kStampWgs * kStampWords;
+  return hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_phase_stamps), bytes < all ? bytes : all) == hipSuccess ? 0 : -1;
+}
+#endif
 
 kt_status kt_profile_reset(void) {
   g_prof_used = 0;

@@ -165,7 +165,11 @@ __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __res
     const double inv_d = 1.0 / (double)d;
     const double m2 = M[0] * inv_d, m3 = M[1] * inv_d, m4 = M[2] * inv_d;
     const double r2 = m2 + mu * mu;
-    const bool ok = m2 > 1e-5 * r2;  // a row this flat counts as having no spread (same rule as the d = 128 kernel)
+    // A row counts as having no spread when its variance is below 1e-10 of its mean square (sigma below 1e-5 of the
+    // mean): fp32 accumulation leaves about 1e-13 there on a row that is constant in exact arithmetic, and a row
+    // with a real spread that small cannot be resolved from fp32 products anyway.  Above the threshold kappa is
+    // returned with an error that grows like 1e-6 |mean| / sigma instead of being silently dropped.
+    const bool ok = m2 > 1e-10 * r2;  // same rule as the d = 128 kernel
     double kappa = 0.0, alpha = 0.0, beta = 0.0;
     if (ok) {
       kappa = m4 / (m2 * m2);

@@ -129,9 +129,9 @@ struct EpiGrad : EpiBase {
 #pragma unroll
           for (int nb = 0; nb < TL::NB; ++nb) {
             const float c = acc[mb][nb][r] - mu[nb];
-            float g = alpha[nb] * fmaf(c, fmaf(c, c, -beta[nb]), -m3[nb]);
-            if (alpha[nb] == 0.f) g = 0.f;
-            v[nb] = from_float<T>(g);
+            // alpha = 0 (padding tokens, rows without spread) gives 0 by itself: the accumulators of padding
+            // tokens come from re-read valid rows and are finite
+            v[nb] = from_float<T>(alpha[nb] * fmaf(c, fmaf(c, c, -beta[nb]), -m3[nb]));
           }
           const int feat = m0 + f.m_of(mb, r);
           *reinterpret_cast<vecT*>(out + (int64_t)feat * tb) = v;

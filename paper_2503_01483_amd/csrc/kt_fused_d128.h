@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
       s4 += __shfl_xor(s4, 32);
       tick(integral_constant<int, 20>{});
       const float m2 = s2 * inv_d, m3 = s3 * inv_d, m4 = s4 * inv_d;
-      const bool ok = valid && m2 > 1e-5f * (m2 + mu * mu);
+      const bool ok = valid && m2 > 1e-10f * (m2 + mu * mu);  // same rule as finalize_rows_kernel
       // branch-free: a degenerate or out-of-range token gets kappa = 0 and no gradient
       const float m2s = ok ? m2 : 1.f;
       const float inv_m2sq = 1.0f / (m2s * m2s);

@@ -142,6 +142,54 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// Launch description of one batched NT GEMM.
+struct GemmShape {
+  const void* A;
+  const void* B;
+  int64_t lda, ldb;
+  int64_t batch_stride_a, batch_stride_b;  // elements
+  int M, N;
+  int tiles_m, tiles_n;
+  int split_k;       // number of K splits (>= 1)
+  int slabs_total;   // K / BK
+  int slabs_per_split;
+  int tiles_total;   // tiles_m * tiles_n * split_k
+  int grid_padded;   // tiles_total rounded up to a multiple of 8
+  int slabs_per_block;             // K blocking of the operand rows (see gemm_mainloop)
+  int64_t block_bytes_a, block_bytes_b;
+  int k_valid;                     // ATN: rows of A that exist (K may be padded beyond them)
+#ifdef KT_PHASE_STAMPS
+  int stamp_slot;                  // developer build only: which launch record the stamps go to
+#endif
+};
+
+#ifdef KT_PHASE_STAMPS
+// Developer build (-DKT_PHASE_STAMPS, never the shipped library): wave 0 of every workgroup records the
+// shader-clock counter at kernel entry, after the prologue, after the main loop and after the epilogue,
+// plus the constant-rate (100 MHz) counter at entry and exit and the hardware id of its CU, so that a
+// launch can be broken down into phases and the clock the chip actually held can be read off.
+constexpr int kStampSlots = 8, kStampWgs = 16384, kStampWords = 8;
+__device__ unsigned long long g_phase_stamps[kStampSlots * kStampWgs * kStampWords];
+__device__ __forceinline__ void phase_stamp(const GemmShape& g, int word, bool wall = false) {
+  if (threadIdx.x != 0 || g.stamp_slot < 0) return;
+  const size_t wg = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+  if (wg >= (size_t)kStampWgs) return;
+  unsigned long long* rec = g_phase_stamps + ((size_t)g.stamp_slot * kStampWgs + wg) * kStampWords;
+  rec[word] = wall ? __builtin_amdgcn_s_memrealtime() : __builtin_readcyclecounter();
+}
+#define KT_STAMP(g, word) phase_stamp(g, word)
+#define KT_STAMP_WALL(g, word) phase_stamp(g, word, true)
+#define KT_STAMP_PARAM , const GemmShape* stamp_g = nullptr
+#define KT_STAMP_ARG , &g
+#define KT_STAMP_LOOP_START() do { if (stamp_g) phase_stamp(*stamp_g, 1); } while (0)
+#else
+#define KT_STAMP(g, word)
+#define KT_STAMP_WALL(g, word)
+#define KT_STAMP_PARAM
+#define KT_STAMP_ARG
+#define KT_STAMP_LOOP_START()
+#endif
+
 // Main loop.  Rows of A beyond M (and of B beyond N) are read from the last valid
 // row, so every load stays inside the operand; the epilogue masks them out.
 // K is addressed in slabs: slab g of an operand row starts at byte
@@ -185,7 +233,8 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
                                               int N, int n0, int slab0, int k_slabs,
                                               int slabs_per_block, int64_t block_bytes_a,
                                               int64_t block_bytes_b,
-                                              floatx16 (&acc)[TL::MB][TL::NB], char* lds, int k_valid = 0) {
+                                              floatx16 (&acc)[TL::MB][TL::NB], char* lds, int k_valid = 0
+                                              KT_STAMP_PARAM) {
   using T = typename TL::T;
   static_assert(!ATN || (sizeof(T) == 2 && TL::BM == 256 && TL::NT == 256), "ATN: bf16, 256 tile rows, 4 waves");
   constexpr int A_STAGE = ATN ? kAtnStageBytes : TL::A_BYTES;
@@ -359,6 +408,7 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   lds_barrier();
   static_for<NFRAG>([&](auto i_c) __attribute__((always_inline)) { fread(P0{}, i_c, P0{}, C0{}); });
   __builtin_amdgcn_sched_barrier(0);
+  KT_STAMP_LOOP_START();
 
   int slab = 0;
   for (; slab + 1 < k_slabs; slab += 2) {
@@ -367,24 +417,6 @@ __device__ __forceinline__ void gemm_mainloop(const typename TL::T* __restrict__
   }
   if (slab < k_slabs) one_slab(P0{}, slab);
 }
-
-// Launch description of one batched NT GEMM.
-struct GemmShape {
-  const void* A;
-  const void* B;
-  int64_t lda, ldb;
-  int64_t batch_stride_a, batch_stride_b;  // elements
-  int M, N;
-  int tiles_m, tiles_n;
-  int split_k;       // number of K splits (>= 1)
-  int slabs_total;   // K / BK
-  int slabs_per_split;
-  int tiles_total;   // tiles_m * tiles_n * split_k
-  int grid_padded;   // tiles_total rounded up to a multiple of 8
-  int slabs_per_block;             // K blocking of the operand rows (see gemm_mainloop)
-  int64_t block_bytes_a, block_bytes_b;
-  int k_valid;                     // ATN: rows of A that exist (K may be padded beyond them)
-};
 
 // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them,
 // each with its own L2), so ids are first regrouped so that each XCD walks a
@@ -417,6 +449,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmShape g, Epi epi) {
   int tm, tn, ks;
   if (!tile_of_block(g, tm, tn, ks)) return;
   if (epi.skip(batch)) return;
+  KT_STAMP_WALL(g, 4);
+  KT_STAMP(g, 0);
   const int m0 = tm * TL::BM, n0 = tn * TL::BN;
   const int slab0 = ks * g.slabs_per_split;
   int slabs = g.slabs_total - slab0;
@@ -433,8 +467,18 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmShape g, Epi epi) {
   const T* A = static_cast<const T*>(g.A) + (int64_t)batch * g.batch_stride_a;
   const T* B = static_cast<const T*>(g.B) + (int64_t)batch * g.batch_stride_b;
   gemm_mainloop<TL, ATN>(A, g.lda, g.M, m0, B, g.ldb, g.N, n0, slab0, slabs, g.slabs_per_block,
-                         g.block_bytes_a, g.block_bytes_b, acc, lds, g.k_valid);
+                         g.block_bytes_a, g.block_bytes_b, acc, lds, g.k_valid KT_STAMP_ARG);
+  KT_STAMP(g, 2);
   epi(acc, batch, tm, tn, ks, m0, n0);
+  KT_STAMP(g, 3);
+  KT_STAMP_WALL(g, 5);
+#ifdef KT_PHASE_STAMPS
+  if (threadIdx.x == 0 && g.stamp_slot >= 0) {
+    const size_t wg = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+    if (wg < (size_t)kStampWgs)
+      g_phase_stamps[((size_t)g.stamp_slot * kStampWgs + wg) * kStampWords + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));
+  }
+#endif
 }
 
 }  // namespace kt

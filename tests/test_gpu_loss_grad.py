@@ -165,6 +165,15 @@ def test_rows_with_a_mean_far_above_their_spread(dtype, d, tol):
         check_loss_grad(gc, oc, tol)
         if dtype == "f32":
             assert np.allclose(gc["row_kurt"], g["row_kurt"], rtol=2e-4)
+    # Further out (sigma down to 3e-4 of the mean) the rows are still resolved, not dropped as flat: the error
+    # of fp32 products grows with mean / sigma (about 1e-6 per unit of it on the fp32 path; the bf16 path's
+    # tolerance covers it).  The oracle treats a row as flat only below 1e-15 of that.
+    for c in (300.0, 1000.0, 3000.0):
+        X = (Z + c * shift_dir).to(torch.float32 if dtype == "f32" else torch.bfloat16)
+        g = gpu_loss_grad(X, R)
+        o = oracle_loss_grad(X, R)
+        assert np.all(o["row_kurt"] > 2.0) and np.all(g["row_kurt"] > 2.0)      # no row counted as flat
+        check_loss_grad(g, o, max(tol, 4e-6 * c))
 
 
 # ---- head-dimension problems (d = 128, bf16) take the single-pass fused kernel -------------------

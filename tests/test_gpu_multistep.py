@@ -1,0 +1,61 @@
+"""The multi-step protocol of the d = 2048 configuration as it is stated (R0 = identity, ten consecutive
+loss + gradient + Cayley steps, lr = 1e-2, bf16 activations with 16 outlier channels x100 and 5 % Student-t
+entries), on a row chunk the oracle can do, teacher-forced: at every step the GPU starts from the ORACLE's
+rotation of that step, so that the two cannot drift apart and each step's outputs can be held to the path
+tolerance (loss and dR 2e-2: bf16 inputs; the retraction 1e-4: fp32).  The first step runs from the identity
+(Y = X exactly), the later ones on the 128 x 128 three-term tiles of the retraction in sequence.
+
+Checked per step: loss and dR against the oracle at the bf16-rounded rotation; the retraction of the oracle's own
+gradient (rounded to fp32) against the oracle's exact solve; the GPU's whole step (its own gradient through its
+own retraction) against the oracle's step; orthogonality.  And over the sequence: the oracle's loss falls."""
+import numpy as np
+import pytest
+import torch
+
+import ktgen
+import oracle
+import paper_2503_01483_amd as kt
+from parity_util import rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c2_protocol_ten_steps_from_the_identity_teacher_forced():
+    rows, steps = 1536, 10
+    X, R, cfg = ktgen.make_problem("C2", seed=0, n=rows)
+    d, lr = cfg["d"], cfg["lr"]
+    assert d == 2048 and cfg["R0"] == "identity" and cfg["steps"] == steps
+    Xd = X.cuda()
+    Xo = ktgen.to_f64(X[0])
+    Ro = ktgen.to_f64(R[0])
+    ws = kt.Workspace()
+    losses = []
+    for k in range(steps):
+        R32 = torch.tensor(Ro, dtype=torch.float32).unsqueeze(0)      # the rotation both sides start this step from
+        Rin = ktgen.to_f64(R32[0])
+        o = oracle.loss_grad(Xo, ktgen.to_f64(ktgen.bf16_round(R32[0])))
+        Rd = R32.cuda()
+        dR = torch.empty_like(Rd)
+        info = torch.zeros(1, dtype=torch.int32, device="cuda")
+        oe = torch.zeros(1, device="cuda")
+        print(f"step {k}: loss+grad, Cayley", flush=True)
+        loss = kt.kt_kurtosis_loss_grad(Xd, Rd, dR=dR, workspace=ws)
+        Rstep = Rd.clone()
+        kt.kt_cayley_step(Rstep, dR, lr, ortho_err=oe, info=info, workspace=ws)
+        G32 = torch.tensor(o["dR"], dtype=torch.float32).unsqueeze(0)
+        Rforced = Rd.clone()
+        kt.kt_cayley_step(Rforced, G32.cuda(), lr, workspace=ws)
+        torch.cuda.synchronize()
+        Rnext = oracle.cayley_step(Rin, ktgen.to_f64(G32[0]), lr)
+
+        assert abs(loss.item() - o["loss"]) <= 2e-2 * o["loss"], k
+        assert rel_fro(dR[0].cpu().numpy(), o["dR"]) <= 2e-2, k
+        assert rel_fro(Rforced[0].cpu().double().numpy() - Rin, Rnext - Rin) <= 1e-4, k
+        assert rel_fro(Rstep[0].cpu().double().numpy() - Rin, Rnext - Rin) <= 2e-2, k
+        assert 1 <= info.item() <= 32 and oe.item() < 1e-6, (k, info.item(), oe.item())
+        losses.append(o["loss"])
+        Ro = Rnext
+    assert losses[-1] < losses[0]
+    RtR = Ro.T @ Ro
+    # the chain passes through fp32 at every step (the rotation both sides start from): each rounding adds ~1e-7
+    assert np.abs(RtR - np.eye(d)).max() < 1e-6
