@@ -1123,8 +1123,11 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
         if (!launch_gemm<TL>(Xp + row0 * ldx, ldx, n * ldx, (int)nt, RT + b0 * d * d, d, d * d, (int)d, d, 0, (int)nb,
                              e, st))
           return fail(KT_ERR_DEVICE, "rotation GEMM launch failed");
-        hipLaunchKernelGGL((quant_metrics_row_kernel<T>), dim3((unsigned)nt, (unsigned)nb), dim3(256),
-                           (size_t)d * 4, st, Yb, Xp + row0 * ldx, ldx, n * ldx, (int)nt, (int)d, (double)quantile,
+        auto rows_kernel = d <= 1024 ? quant_metrics_row_kernel<T, 4>
+                           : d <= 4096 ? quant_metrics_row_kernel<T, 16> : quant_metrics_row_kernel<T, 32>;
+        const int64_t row_wgs = ceil_div(nt, 4) < ceil_div(16 * kNumCUs, nb) ? ceil_div(nt, 4) : ceil_div(16 * kNumCUs, nb);
+        hipLaunchKernelGGL(rows_kernel, dim3((unsigned)row_wgs, (unsigned)nb), dim3(256), 0, st, Yb,
+                           Xp + row0 * ldx, ldx, n * ldx, (int)nt, (int)d, (double)quantile,
                            amax ? amax + 2 * row0 : nullptr, threshold ? threshold + row0 : nullptr,
                            err_sym ? err_sym + 2 * row0 : nullptr, err_asym ? err_asym + 2 * row0 : nullptr,
                            success ? reinterpret_cast<unsigned long long*>(success) + b0 : nullptr);

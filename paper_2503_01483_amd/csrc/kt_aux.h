@@ -708,9 +708,17 @@ __device__ __forceinline__ unsigned block_umin_256(unsigned v, unsigned* red4) {
   return a < b ? a : b;
 }
 
-// grid = (n, batch); dynamic LDS = d * 4 bytes.  Y [batch][n][d] fp32.
-template <typename TX>
-__global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __restrict__ Y,
+// One WAVE per token row, the row in registers (NV4 float4 per lane: d <= 256 NV4), no workgroup barrier:
+// the four waves of a workgroup work on four rows independently, all 4 NV4 loads of a row are in flight at
+// once, and the reductions are wave shuffles.  The quantile needs two order statistics of |y|: a 4 x 8-bit
+// radix select on the bit patterns (integer work, bit-exact), on a 256-bin histogram of the wave's own in
+// LDS (a lane counts runs of equal bins privately and touches the histogram when the bin changes; lane l
+// then scans bins 4l .. 4l+3 and a wave prefix sum finds the bin of rank k).
+// grid = (ceil(n / 4), batch).  Y [batch][n][d] fp32.
+// (second launch bound: waves per SIMD the register allocation must leave room for, so that the loads of
+// several rows are in flight per SIMD; the row itself takes 4 NV4 registers)
+template <typename TX, int NV4>
+__global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant_metrics_row_kernel(const float* __restrict__ Y,
                                                                 const TX* __restrict__ X, int64_t ldx,
                                                                 int64_t x_batch_stride, int n, int d,
                                                                 double quant, float* __restrict__ amax_out,
@@ -718,35 +726,71 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
                                                                 float* __restrict__ err_sym,
                                                                 float* __restrict__ err_asym,
                                                                 unsigned long long* __restrict__ success) {
-  extern __shared__ __align__(16) float row[];
-  __shared__ unsigned hist[256];
-  __shared__ double shd[4];
-  __shared__ float red4[4];
-  __shared__ unsigned ured4[4];
-  __shared__ unsigned sel[2];
-  const int tid = threadIdx.x, batch = blockIdx.y, token = blockIdx.x;
-  const float* y = Y + ((int64_t)batch * n + token) * d;
+  __shared__ unsigned hist_all[4][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, batch = blockIdx.y;
+  volatile unsigned* hist = hist_all[wave];
+  unsigned wins = 0u;  // rows of this wave whose largest magnitude shrank: one atomic per wave, not per row
+  // a wave walks rows token, token + 4 gridDim.x, ...; whole waves leave the loop, nothing synchronises across waves
+#pragma unroll 1
+  for (int token = blockIdx.x * 4 + wave; token < n; token += 4 * (int)gridDim.x) {
+  const float4* y4 = reinterpret_cast<const float4*>(Y + ((int64_t)batch * n + token) * d);
   const TX* x = X + (int64_t)batch * x_batch_stride + (int64_t)token * ldx;
-  float ab = 0.f, ar = 0.f, mn = 3.0e38f, mx = -3.0e38f;
-  double y2 = 0.0;
-  for (int j = tid; j < d; j += 256) {
-    const float v = y[j];
-    row[j] = v;
-    ab = fmaxf(ab, fabsf((float)x[j]));
-    ar = fmaxf(ar, fabsf(v));
-    mn = fminf(mn, v);
-    mx = fmaxf(mx, v);
-    y2 += (double)v * (double)v;
+  // chunk c holds values 256 c + 4 lane .. + 3; d is a multiple of 128, so the last chunk may be half full
+  auto live = [&](int c) __attribute__((always_inline)) { return 256 * c + 4 * lane < d; };
+  float4 v[NV4];
+#pragma unroll
+  for (int c = 0; c < NV4; ++c) {
+    v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live(c)) v[c] = y4[c * 64 + lane];
   }
-  ab = block_fmax_256(ab, red4);
-  ar = block_fmax_256(ar, red4);
-  mx = block_fmax_256(mx, red4);
-  mn = -block_fmax_256(-mn, red4);
-  const double y2t = block_dsum_fast_256(y2, shd);
+  // largest magnitude of the unrotated row: all of this lane's 16-byte loads are requested before the first
+  // is used (a loop that waits for each load in turn costs a memory latency per 16 bytes)
+  float ab = 0.f;
+  {
+    constexpr int EPC = 16 / (int)sizeof(TX);                       // elements per 16 bytes
+    constexpr int NXV = (NV4 * (int)sizeof(TX) + 3) / 4;            // 16-byte chunks per lane: d <= 64 NXV EPC
+    typedef TX vecx __attribute__((ext_vector_type(16 / sizeof(TX))));
+    vecx xv[NXV];
+#pragma unroll
+    for (int c = 0; c < NXV; ++c) {
+      const int j = (c * 64 + lane) * EPC;
+      if (j < d) xv[c] = *reinterpret_cast<const vecx*>(x + j);
+      else {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) xv[c][e] = (TX)0.0f;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < NXV; ++c)
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) ab = fmaxf(ab, fabsf((float)xv[c][e]));
+  }
+  float ar = 0.f, mn = 3.0e38f, mx = -3.0e38f;
+  double y2 = 0.0;
+#pragma unroll
+  for (int c = 0; c < NV4; ++c) {
+    if (live(c)) {
+      const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        ar = fmaxf(ar, fabsf(e4[e]));
+        mn = fminf(mn, e4[e]);
+        mx = fmaxf(mx, e4[e]);
+        y2 = fma((double)e4[e], (double)e4[e], y2);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    ab = fmaxf(ab, __shfl_xor(ab, o));
+    ar = fmaxf(ar, __shfl_xor(ar, o));
+    mn = fminf(mn, __shfl_xor(mn, o));
+    mx = fmaxf(mx, __shfl_xor(mx, o));
+    y2 += __shfl_xor(y2, o);
+  }
 
   float t = ar;
   if (quant < 1.0) {
-    // order statistics k and k+1 (ascending) of |y| by a 4 x 8-bit radix select on the bit patterns
     const double pos = quant * (double)(d - 1);
     const int k = (int)floor(pos);
     const float frac = (float)(pos - (double)k);
@@ -754,63 +798,82 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
     int kk = k;
 #pragma unroll 1
     for (int shift = 24; shift >= 0; shift -= 8) {
-      hist[tid] = 0u;
-      __syncthreads();
-      // the high digits of a row's magnitudes fall into very few bins: count runs privately and
-      // touch the shared histogram only when the bin changes
+      hist[4 * lane] = 0u; hist[4 * lane + 1] = 0u; hist[4 * lane + 2] = 0u; hist[4 * lane + 3] = 0u;
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
       unsigned run_bin = 0xffffffffu, run_cnt = 0u;
-      for (int j = tid; j < d; j += 256) {
-        const unsigned u = __float_as_uint(fabsf(row[j]));
-        if ((u & mask) == prefix) {
-          const unsigned bin = (u >> shift) & 255u;
-          if (bin == run_bin) {
-            run_cnt += 1u;
-          } else {
-            if (run_cnt) atomicAdd(&hist[run_bin], run_cnt);
-            run_bin = bin;
-            run_cnt = 1u;
-          }
-        }
-      }
-      if (run_cnt) atomicAdd(&hist[run_bin], run_cnt);
-      __syncthreads();
-      if (tid < 64) {  // wave 0: lane l owns bins 4l .. 4l+3; prefix scan over the lanes
-        const unsigned c0 = hist[4 * tid], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
-        const unsigned own = c0 + c1 + c2 + c3;
-        unsigned incl = own;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const unsigned up = (unsigned)__shfl_up((int)incl, o);
-          if (tid >= o) incl += up;
+      for (int c = 0; c < NV4; ++c) {
+        const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+        unsigned bin[4];
+        bool m[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const unsigned u = __float_as_uint(fabsf(e4[e]));
+          m[e] = live(c) && (u & mask) == prefix;
+          bin[e] = (u >> shift) & 255u;
         }
-        const unsigned excl = incl - own;
-        if (excl <= (unsigned)kk && (unsigned)kk < incl) {  // exactly one lane (the counts sum to > kk)
-          unsigned cum = excl;
-          int b = 4 * tid;
-          if (cum + c0 <= (unsigned)kk) { cum += c0; ++b;
-            if (cum + c1 <= (unsigned)kk) { cum += c1; ++b;
-              if (cum + c2 <= (unsigned)kk) { cum += c2; ++b; } } }
-          sel[0] = (unsigned)b;
-          sel[1] = cum;
+        // in the later rounds hardly any value still matches the prefix: skip the chunk for the whole wave
+        if (!__any((int)(m[0] | m[1] | m[2] | m[3]))) continue;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool same = m[e] && bin[e] == run_bin;
+          const bool change = m[e] && !same;
+          if (change && run_cnt) atomicAdd(const_cast<unsigned*>(&hist[run_bin]), run_cnt);
+          run_cnt = same ? run_cnt + 1u : (change ? 1u : run_cnt);
+          run_bin = change ? bin[e] : run_bin;
         }
       }
-      __syncthreads();
-      prefix |= sel[0] << shift;
-      kk -= (int)sel[1];
+      if (run_cnt) atomicAdd(const_cast<unsigned*>(&hist[run_bin]), run_cnt);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      // lane l owns bins 4l .. 4l+3; prefix scan over the lanes
+      const unsigned c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+      const unsigned own = c0 + c1 + c2 + c3;
+      unsigned incl = own;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned up = (unsigned)__shfl_up((int)incl, o);
+        if (lane >= o) incl += up;
+      }
+      const unsigned excl = incl - own;
+      const bool hit = excl <= (unsigned)kk && (unsigned)kk < incl;  // exactly one lane (the counts sum to > kk)
+      unsigned cum = excl;
+      int bsel = 4 * lane;
+      if (cum + c0 <= (unsigned)kk) { cum += c0; ++bsel;
+        if (cum + c1 <= (unsigned)kk) { cum += c1; ++bsel;
+          if (cum + c2 <= (unsigned)kk) { cum += c2; ++bsel; } } }
+      const unsigned long long hits = __ballot(hit);
+      const int src = hits ? __builtin_ctzll(hits) : 0;
+      const unsigned sel_bin = (unsigned)__shfl(bsel, src);
+      const unsigned sel_cum = (unsigned)__shfl((int)cum, src);
+      prefix |= sel_bin << shift;
+      kk -= (int)sel_cum;
       mask |= 255u << shift;
-      __syncthreads();
+      __builtin_amdgcn_wave_barrier();
     }
     // prefix = bits of a_k; a_{k+1} = a_k if enough copies of it, else the smallest larger value
     unsigned le = 0u, nxt = 0xffffffffu;
-    for (int j = tid; j < d; j += 256) {
-      const unsigned u = __float_as_uint(fabsf(row[j]));
-      if (u <= prefix) le += 1u;
-      else if (u < nxt) nxt = u;
+#pragma unroll
+    for (int c = 0; c < NV4; ++c) {
+      if (live(c)) {
+        const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const unsigned u = __float_as_uint(fabsf(e4[e]));
+          if (u <= prefix) le += 1u;
+          else if (u < nxt) nxt = u;
+        }
+      }
     }
-    const double le_t = block_dsum_fast_256((double)le, shd);
-    nxt = block_umin_256(nxt, ured4);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      le += (unsigned)__shfl_xor((int)le, o);
+      const unsigned w = (unsigned)__shfl_xor((int)nxt, o);
+      nxt = w < nxt ? w : nxt;
+    }
     const float ak = __uint_as_float(prefix);
-    const float ak1 = ((int)le_t >= k + 2 || nxt == 0xffffffffu) ? ak : __uint_as_float(nxt);
+    const float ak1 = ((int)le >= k + 2 || nxt == 0xffffffffu) ? ak : __uint_as_float(nxt);
     float inc = __fmul_rn(frac, __fsub_rn(ak1, ak));
     asm volatile("" : "+v"(inc));  // keep the product rounded: no contraction with the add below
     t = __fadd_rn(ak, inc);
@@ -819,28 +882,42 @@ __global__ __launch_bounds__(256) void quant_metrics_row_kernel(const float* __r
   const float rs = ss > 0.f ? __fdiv_rn(1.0f, ss) : 0.f;
   const float sa = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
   const float ra = sa > 0.f ? __fdiv_rn(1.0f, sa) : 0.f;
+  const double ssd = (double)ss, sad = (double)sa, mnd = (double)mn;
   double es = 0.0, ea = 0.0;
-  for (int j = tid; j < d; j += 256) {
-    const float v = row[j];
-    float q = rintf(__fmul_rn(v, rs));
-    q = fminf(fmaxf(q, -7.f), 7.f);
-    const double dsym = (double)v - (double)q * (double)ss;
-    es += dsym * dsym;
-    float qa = rintf(__fmul_rn(__fsub_rn(v, mn), ra));
-    qa = fminf(fmaxf(qa, 0.f), 15.f);
-    const double dasy = (double)v - ((double)qa * (double)sa + (double)mn);
-    ea += dasy * dasy;
+#pragma unroll
+  for (int c = 0; c < NV4; ++c) {
+    if (live(c)) {
+      const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float val = e4[e];
+        const double vd = (double)val;
+        float q = rintf(__fmul_rn(val, rs));
+        q = __builtin_amdgcn_fmed3f(q, -7.f, 7.f);
+        const double dsym = fma(-(double)q, ssd, vd);
+        es = fma(dsym, dsym, es);
+        float qa = rintf(__fmul_rn(__fsub_rn(val, mn), ra));
+        qa = __builtin_amdgcn_fmed3f(qa, 0.f, 15.f);
+        const double dasy = vd - fma((double)qa, sad, mnd);
+        ea = fma(dasy, dasy, ea);
+      }
+    }
   }
-  const double est = block_dsum_fast_256(es, shd);
-  const double eat = block_dsum_fast_256(ea, shd);
-  if (tid == 0) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    es += __shfl_xor(es, o);
+    ea += __shfl_xor(ea, o);
+  }
+  if (lane == 0) {
     const int64_t o = (int64_t)batch * n + token;
     if (amax_out) { amax_out[2 * o] = ab; amax_out[2 * o + 1] = ar; }
     if (thr_out) thr_out[o] = t;
-    if (err_sym) { err_sym[2 * o] = (float)est; err_sym[2 * o + 1] = (float)y2t; }
-    if (err_asym) { err_asym[2 * o] = (float)eat; err_asym[2 * o + 1] = (float)y2t; }
-    if (success && ar < ab) atomicAdd(&success[batch], 1ull);
+    if (err_sym) { err_sym[2 * o] = (float)es; err_sym[2 * o + 1] = (float)y2; }
+    if (err_asym) { err_asym[2 * o] = (float)ea; err_asym[2 * o + 1] = (float)y2; }
+    if (ar < ab) wins += 1u;
   }
+  }
+  if (lane == 0 && success && wins) atomicAdd(&success[batch], (unsigned long long)wins);
 }
 
 // Plain fp32 matrix transpose out[c][r] = in[r][c] (rows x cols -> cols x rows), 32 x 32 tiles
