@@ -82,6 +82,44 @@ class ClockSampler:
                 "source": "sysfs pp_dpm_sclk / hwmon power1_input polled by a host thread during the timed steps"}
 
 
+def phase_stamps(kt, step, d, n):
+    """One step with the GEMM kernel's own time stamps (wave 0 of every workgroup: shader-clock counter at entry,
+    after the prologue, after the main loop, after the epilogue; the 100 MHz counter at entry and exit)."""
+    import ctypes
+    import numpy as np
+    L = kt.lib()
+    if not hasattr(L, "kt_debug_stamps_arm"):
+        sys.exit("bench.py --phase-stamps: the library was not built with -DKT_PHASE_STAMPS")
+    slots, wgs, words = 8, 16384, 8
+    buf = np.zeros(slots * wgs * words, dtype=np.uint64)
+    L.kt_debug_stamps_arm()
+    step()
+    L.kt_debug_stamps_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    assert L.kt_debug_stamps_read(buf.ctypes.data_as(ctypes.c_void_p), buf.nbytes) == 0
+    r_all = buf.reshape(slots, wgs, words).astype(np.int64)
+    names = ["forward + row moments", "recompute + dL/dY", "dR = X^T G", "Cayley: M = dR R^T", "Cayley iteration 1",
+             "Cayley iteration 2", "Cayley iteration 3", "Cayley iteration 4"]
+    out = []
+    for s in range(slots):
+        r = r_all[s][r_all[s][:, 3] > 0]
+        if not len(r):
+            continue
+        pro, loop, epi, tot = r[:, 1] - r[:, 0], r[:, 2] - r[:, 1], r[:, 3] - r[:, 2], r[:, 3] - r[:, 0]
+        wall_us = (r[:, 5] - r[:, 4]) / 100.0
+        span_us = (r[:, 5].max() - r[:, 4].min()) / 100.0
+        rec = {"launch": names[s], "workgroups": int(len(r)), "span_us": round(float(span_us), 1),
+               "share_prologue": round(float(pro.sum() / tot.sum()), 4), "share_main_loop": round(float(loop.sum() / tot.sum()), 4),
+               "share_epilogue": round(float(epi.sum() / tot.sum()), 4),
+               "cycles_per_workgroup_median": {"prologue": int(np.median(pro)), "main_loop": int(np.median(loop)), "epilogue": int(np.median(epi))},
+               "shader_clock_mhz_median": round(float(np.median(tot / np.maximum(wall_us, 1e-9))), 0),
+               "cu_occupancy_of_span": round(float(wall_us.sum() / (span_us * 256)), 4)}
+        if s < 3:  # K slabs x 64 matrix instructions per wave x 32 cycles each, back to back
+            k = d if s < 2 else n
+            rec["main_loop_efficiency"] = round(float((k / 64) * 64 * 32 / np.median(loop)), 4)
+        out.append(rec)
+    print(json.dumps({"phase_stamps": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +140,10 @@ def main():
                          "with RMSNorm (kappa_target 1.8)")
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
                     help="retraction timed inside the step: Cayley SGD (default, the headline step) or Cayley Adam")
+    ap.add_argument("--phase-stamps", action="store_true",
+                    help="developer builds only (KT_HIPCC_EXTRA=-DKT_PHASE_STAMPS python -m paper_2503_01483_amd.build): "
+                         "after the warm-up run ONE step with the in-kernel time stamps armed and print, per GEMM "
+                         "launch, the share of prologue / main loop / epilogue and the shader clock the stamps imply")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after timing, copy X once with a plain device copy (a kernel of known traffic, "
                          "2 x bytes(X), against which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled)")
@@ -195,6 +237,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.phase_stamps:
+        phase_stamps(kt, step, d, n)
+        return
     loss_first = loss.clone()
     kt.kt_profile_enable(8 * args.steps + 8)
     kt.kt_profile_reset()

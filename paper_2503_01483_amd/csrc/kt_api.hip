@@ -2,10 +2,12 @@
 // sequences, and the extern "C" boundary declared in include/kt.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "../../include/kt.h"
@@ -84,16 +86,21 @@ static void* static_scratch_of_current_device() {
 
 // ------------------------------------------------------------------ profiling -----
 // Optional event brackets around the large launches (see kt_profile_enable).
+// Entry points running on several host threads may take records at the same time: the slot counter is
+// atomic (a slot belongs to the scope that drew it); enabling, reading and resetting are not, as the header says.
 struct ProfRecord { hipEvent_t start, stop; int id; };
 static ProfRecord* g_prof = nullptr;
-static int g_prof_cap = 0, g_prof_used = 0;
+static int g_prof_cap = 0;
+static std::atomic<int> g_prof_used{0};
 
 struct ProfScope {
   ProfRecord* rec = nullptr;
   hipStream_t st;
   ProfScope(int id, hipStream_t s) : st(s) {
-    if (g_prof && g_prof_used < g_prof_cap) {
-      rec = &g_prof[g_prof_used++];
+    if (g_prof && g_prof_used.load(std::memory_order_relaxed) < g_prof_cap) {
+      const int slot = g_prof_used.fetch_add(1, std::memory_order_relaxed);
+      if (slot >= g_prof_cap) return;  // another thread drew the last slot meanwhile
+      rec = &g_prof[slot];
       rec->id = id;
       (void)hipEventRecord(rec->start, st);
     }
@@ -1252,7 +1259,7 @@ int kt_debug_stamps_read(void* host_dst, size_t bytes) {
 #endif
 
 kt_status kt_profile_reset(void) {
-  g_prof_used = 0;
+  g_prof_used.store(0);
   return KT_OK;
 }
 
@@ -1265,9 +1272,11 @@ kt_status kt_profile_enable(int32_t max_records) {
   }
   delete[] g_prof;
   g_prof = nullptr;
-  g_prof_cap = g_prof_used = 0;
+  g_prof_cap = 0;
+  g_prof_used.store(0);
   if (max_records == 0) return KT_OK;
-  g_prof = new ProfRecord[max_records];
+  g_prof = new (std::nothrow) ProfRecord[max_records];  // no exception may cross the C boundary
+  if (!g_prof) return fail(KT_ERR_INVALID_ARG, "cannot hold %d profile records", (int)max_records);
   for (int i = 0; i < max_records; ++i) {
     if (hipEventCreate(&g_prof[i].start) != hipSuccess || hipEventCreate(&g_prof[i].stop) != hipSuccess)
       return fail(KT_ERR_DEVICE, "hipEventCreate failed");
@@ -1281,7 +1290,8 @@ kt_status kt_profile_read(int32_t kernel_id, double* total_ms, int32_t* launches
   if (!total_ms || !launches) return fail(KT_ERR_INVALID_ARG, "outputs must not be null");
   double tot = 0.0;
   int cnt = 0;
-  for (int i = 0; i < g_prof_used; ++i) {
+  const int used = g_prof_used.load() < g_prof_cap ? g_prof_used.load() : g_prof_cap;
+  for (int i = 0; i < used; ++i) {
     if (g_prof[i].id != kernel_id) continue;
     if (hipEventSynchronize(g_prof[i].stop) != hipSuccess) return fail(KT_ERR_DEVICE, "event sync failed");
     float ms = 0.f;
