@@ -208,22 +208,31 @@ __global__ __launch_bounds__(256) void fused_d128_kernel(const __bf16* __restric
     const char* xbase = lds + xbuf_r * BUF;
     const char* gbase = lds + kF128GOff + gbuf_r * BUF;
     intx4 fa[2][2], fb[2][2];
-    auto fread = [&](auto s_c) __attribute__((always_inline)) {
-      constexpr int s = decltype(s_c)::value;
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib)
+    // one operand of K sub-step s (two transposing reads): 0 X block 0, 1 G block 0, 2 G block 1, 3 X block 1
+    auto fread_one = [&](auto s_c, auto which_c) __attribute__((always_inline)) {
+      constexpr int s = decltype(s_c)::value, which = decltype(which_c)::value;
+      if constexpr (which == 0 || which == 3) {
+        constexpr int ib = which == 0 ? 0 : 1;
         fa[s & 1][ib] = read_tr_operand(xbase, xa_lo[ib] + s * 16 * 256, xa_hi[ib] + s * 16 * 256);
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+      } else {
+        constexpr int jb = which - 1;
         fb[s & 1][jb] = read_tr_operand(gbase, gb_lo[s & 1][jb] + s * 16 * 256, gb_hi[s & 1][jb] + s * 16 * 256);
+      }
     };
-    // matrix instruction k of E: K sub-step k / 4, dR block (k / 2) & 1, k & 1
+    auto fread = [&](auto s_c) __attribute__((always_inline)) {
+      static_for<4>([&](auto w_c) __attribute__((always_inline)) { fread_one(s_c, w_c); });
+    };
+    // matrix instruction k of E: K sub-step k / 4, dR block (k / 2) & 1, k & 1.  The four operands of the next
+    // sub-step are read one per instruction slot, BEHIND the slot's matrix instruction and in the order the next
+    // sub-step uses them: never more than eight LDS reads are in flight, so the wait in front of a matrix
+    // instruction can name exactly the reads it needs (the counter has four bits: with all sixteen reads of a
+    // sub-step issued at once, every fourth matrix instruction also waited for reads it did not need).
     auto tick = [&](auto k_c) __attribute__((always_inline)) {
       if constexpr (WITH_E) {
         constexpr int k = decltype(k_c)::value, s = k >> 2, ib = (k >> 1) & 1, jb = k & 1;
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr ((k & 3) == 0 && s + 1 < 8) fread(integral_constant<int, s + 1>{});
         mfma_dr(acc2[ib][jb], fa[s & 1][ib], fb[s & 1][jb]);
+        if constexpr (s + 1 < 8) fread_one(integral_constant<int, s + 1>{}, integral_constant<int, k & 3>{});
         __builtin_amdgcn_sched_barrier(0);
       }
     };
