@@ -141,9 +141,11 @@ def test_c2_c5_full_size(name, rows_checked, chunk):
 
 
 def test_c5_size_cayley_step_against_a_double_precision_solve():
-    """d = 8192 (the C5 rotation): too large for the CPU oracle's plain LU in test time, so the step is
-    compared with the same formula evaluated by the framework's fp64 solver on the device
-    (R+ = (I + lr/2 A)^-1 (I - lr/2 A) R, A = G R^T - R G^T), an independent library routine."""
+    """SECONDARY check (not against the oracle): d = 8192 (the C5 rotation) is too large for the CPU oracle's
+    plain LU in test time, so the step is compared with the same formula evaluated by the framework's fp64
+    solver on the device (R+ = (I + lr/2 A)^-1 (I - lr/2 A) R, A = G R^T - R G^T), a library routine that is
+    independent of the HIP path.  The comparison with the oracle itself, on the same tile path (256 x 256,
+    three-term products), is test_gpu_cayley.py::test_d4096_headline_tiles_against_oracle."""
     d, lr = 8192, 1e-2
     R = ktgen.random_orthogonal(d, seed=2, device="cuda").unsqueeze(0).contiguous()
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -246,8 +248,8 @@ def test_maximum_token_count(d, dtype):
 
 def test_maximum_hidden_size():
     """d = 16384, the largest hidden size the boundary accepts: loss and gradient of a few token rows
-    against the oracle at that d, and a Cayley step against the framework's fp64 solve (as for
-    d = 8192 above); d = 16384 + 128 is refused."""
+    against the oracle at that d, and a Cayley step against the framework's fp64 solve (a SECONDARY check, as
+    for d = 8192 above: the oracle's LU is out of reach at this size); d = 16384 + 128 is refused."""
     d, n, lr = 16384, 16, 1e-2
     g = torch.Generator(device="cuda").manual_seed(11)
     q, r = torch.linalg.qr(torch.randn((d, d), generator=g, device="cuda"))
