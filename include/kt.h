@@ -257,7 +257,8 @@ kt_status kt_rotate_fakequant_int4(const void* X, int64_t ldx, const void* R, in
  *   Y         [batch][n][d] fp32: receives the rotated activations, or NULL (then they live in
  *             the workspace).  Every output pointer may be NULL.
  * Y is materialised (this is an evaluation tool, not the training step): one GEMM pass, then one
- * workgroup per token with the row in LDS (radix select for the quantile).  d <= 8192.
+ * wave per token with the row in registers (radix select on the bit patterns for the quantile).
+ * d <= 8192.
  * Workspace: kt_workspace_bytes(KT_OP_QUANT_METRICS, ...) (sized for Y == NULL: the rotated rows then
  * pass through an fp32 staging slice of at most 1 GiB, a few problems or token rows at a time).
  */

@@ -1095,7 +1095,7 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
   kt_status s = check_xr(X, ldx, R, ldr, batch, n, d, x_dtype, r_dtype);
   if (s != KT_OK) return s;
   if (!(quantile > 0.f && quantile <= 1.f)) return fail(KT_ERR_INVALID_ARG, "quantile must be in (0, 1]");
-  if (d > 8192) return fail(KT_ERR_NOT_SUPPORTED, "quantisation metrics keep a token row in LDS: d <= 8192");
+  if (d > 8192) return fail(KT_ERR_NOT_SUPPORTED, "quantisation metrics keep a token row in registers: d <= 8192");
   const bool fp32 = x_dtype == KT_F32;
   const size_t rt_bytes = (size_t)round_up(batch * d * d * (fp32 ? 4 : 2), 256);
   // With Y wanted the whole rotation is one launch pair into the caller's buffer; without it Y passes through
@@ -1130,8 +1130,15 @@ kt_status kt_rotate_quant_metrics(const void* X, int64_t ldx, const void* R, int
         if (!launch_gemm<TL>(Xp + row0 * ldx, ldx, n * ldx, (int)nt, RT + b0 * d * d, d, d * d, (int)d, d, 0, (int)nb,
                              e, st))
           return fail(KT_ERR_DEVICE, "rotation GEMM launch failed");
-        auto rows_kernel = d <= 1024 ? quant_metrics_row_kernel<T, 4>
-                           : d <= 4096 ? quant_metrics_row_kernel<T, 16> : quant_metrics_row_kernel<T, 32>;
+        // the row in 4 / 8 / 16 / 32 float4 registers per lane; rows that fill them exactly skip every bounds test
+        auto rows_kernel = d == 1024   ? quant_metrics_row_kernel<T, 4, true>
+                           : d < 1024  ? quant_metrics_row_kernel<T, 4, false>
+                           : d == 2048 ? quant_metrics_row_kernel<T, 8, true>
+                           : d < 2048  ? quant_metrics_row_kernel<T, 8, false>
+                           : d == 4096 ? quant_metrics_row_kernel<T, 16, true>
+                           : d < 4096  ? quant_metrics_row_kernel<T, 16, false>
+                           : d == 8192 ? quant_metrics_row_kernel<T, 32, true>
+                                       : quant_metrics_row_kernel<T, 32, false>;
         const int64_t row_wgs = ceil_div(nt, 4) < ceil_div(16 * kNumCUs, nb) ? ceil_div(nt, 4) : ceil_div(16 * kNumCUs, nb);
         hipLaunchKernelGGL(rows_kernel, dim3((unsigned)row_wgs, (unsigned)nb), dim3(256), 0, st, Yb,
                            Xp + row0 * ldx, ldx, n * ldx, (int)nt, (int)d, (double)quantile,

@@ -708,16 +708,19 @@ __device__ __forceinline__ unsigned block_umin_256(unsigned v, unsigned* red4) {
   return a < b ? a : b;
 }
 
-// One WAVE per token row, the row in registers (NV4 float4 per lane: d <= 256 NV4), no workgroup barrier:
-// the four waves of a workgroup work on four rows independently, all 4 NV4 loads of a row are in flight at
-// once, and the reductions are wave shuffles.  The quantile needs two order statistics of |y|: a 4 x 8-bit
-// radix select on the bit patterns (integer work, bit-exact), on a 256-bin histogram of the wave's own in
-// LDS (a lane counts runs of equal bins privately and touches the histogram when the bin changes; lane l
-// then scans bins 4l .. 4l+3 and a wave prefix sum finds the bin of rank k).
-// grid = (ceil(n / 4), batch).  Y [batch][n][d] fp32.
+// One WAVE per token row, the row in registers (NV4 float4 per lane: d <= 256 NV4; FULL: d = 256 NV4, no
+// bounds tests), no workgroup barrier: the four waves of a workgroup work on four rows independently, all
+// loads of a row are in flight at once, and the reductions are wave shuffles.  The quantile needs two order
+// statistics of |y|: a radix select on the bit patterns (integer work, bit-exact) in three rounds of 11, 11
+// and 9 bits, each a histogram of up to 2048 bins that the wave keeps in LDS (one LDS atomic per value that
+// still matches the bits decided so far; in the later rounds whole 256-value pieces are skipped).
+// grid = (row workgroups, batch); a wave walks several rows.  Y [batch][n][d] fp32.
+// Error sums: the difference y - q s as one fused multiply-add in fp32 (exact before its single rounding),
+// squares summed four at a time in fp32 and then in fp64; the asymmetric difference, whose terms cancel
+// from the size of the row's range, in fp64 throughout.
 // (second launch bound: waves per SIMD the register allocation must leave room for, so that the loads of
 // several rows are in flight per SIMD; the row itself takes 4 NV4 registers)
-template <typename TX, int NV4>
+template <typename TX, int NV4, bool FULL>
 __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant_metrics_row_kernel(const float* __restrict__ Y,
                                                                 const TX* __restrict__ X, int64_t ldx,
                                                                 int64_t x_batch_stride, int n, int d,
@@ -726,58 +729,61 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
                                                                 float* __restrict__ err_sym,
                                                                 float* __restrict__ err_asym,
                                                                 unsigned long long* __restrict__ success) {
-  __shared__ unsigned hist_all[4][256];
+  __shared__ __align__(16) unsigned hist_all[4][2048];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, batch = blockIdx.y;
-  volatile unsigned* hist = hist_all[wave];
+  unsigned* hist = hist_all[wave];
   unsigned wins = 0u;  // rows of this wave whose largest magnitude shrank: one atomic per wave, not per row
-  // a wave walks rows token, token + 4 gridDim.x, ...; whole waves leave the loop, nothing synchronises across waves
-#pragma unroll 1
-  for (int token = blockIdx.x * 4 + wave; token < n; token += 4 * (int)gridDim.x) {
-  const float4* y4 = reinterpret_cast<const float4*>(Y + ((int64_t)batch * n + token) * d);
-  const TX* x = X + (int64_t)batch * x_batch_stride + (int64_t)token * ldx;
-  // chunk c holds values 256 c + 4 lane .. + 3; d is a multiple of 128, so the last chunk may be half full
-  auto live = [&](int c) __attribute__((always_inline)) { return 256 * c + 4 * lane < d; };
-  float4 v[NV4];
+  constexpr int EPC = 16 / (int)sizeof(TX);             // elements of X per 16 bytes
+  constexpr int NXV = (NV4 * (int)sizeof(TX) + 3) / 4;  // 16-byte pieces of the X row per lane: d <= 64 NXV EPC
+  typedef TX vecx __attribute__((ext_vector_type(16 / sizeof(TX))));
+  // piece c of a row holds values 256 c + 4 lane .. + 3; d is a multiple of 128, so the last piece may be half full
+  auto live = [&](int c) __attribute__((always_inline)) { return FULL || 256 * c + 4 * lane < d; };
+  // every 16-byte load of a row (Y and X) is requested at once; nothing here waits for them
+  auto load_row = [&](float4 (&v)[NV4], vecx (&xv)[NXV], int token) __attribute__((always_inline)) {
+    const float4* y4 = reinterpret_cast<const float4*>(Y + ((int64_t)batch * n + token) * d);
+    const TX* x = X + (int64_t)batch * x_batch_stride + (int64_t)token * ldx;
 #pragma unroll
-  for (int c = 0; c < NV4; ++c) {
-    v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (live(c)) v[c] = y4[c * 64 + lane];
-  }
-  // largest magnitude of the unrotated row: all of this lane's 16-byte loads are requested before the first
-  // is used (a loop that waits for each load in turn costs a memory latency per 16 bytes)
-  float ab = 0.f;
-  {
-    constexpr int EPC = 16 / (int)sizeof(TX);                       // elements per 16 bytes
-    constexpr int NXV = (NV4 * (int)sizeof(TX) + 3) / 4;            // 16-byte chunks per lane: d <= 64 NXV EPC
-    typedef TX vecx __attribute__((ext_vector_type(16 / sizeof(TX))));
-    vecx xv[NXV];
+    for (int c = 0; c < NV4; ++c) {
+      v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (live(c)) v[c] = y4[c * 64 + lane];
+    }
 #pragma unroll
     for (int c = 0; c < NXV; ++c) {
       const int j = (c * 64 + lane) * EPC;
-      if (j < d) xv[c] = *reinterpret_cast<const vecx*>(x + j);
+      if (FULL || j < d) xv[c] = *reinterpret_cast<const vecx*>(x + j);
       else {
 #pragma unroll
         for (int e = 0; e < EPC; ++e) xv[c][e] = (TX)0.0f;
       }
     }
+  };
+  // a wave walks rows token, token + 4 gridDim.x, ...; whole waves leave the loop, nothing synchronises across waves
+  const int stride = 4 * (int)gridDim.x;
+  float4 v[NV4];
+  vecx xv[NXV];
+#pragma unroll 1
+  for (int token = blockIdx.x * 4 + wave; token < n; token += stride) {
+  load_row(v, xv, token);
+  float ab = 0.f;  // largest magnitude of the unrotated row
 #pragma unroll
-    for (int c = 0; c < NXV; ++c)
+  for (int c = 0; c < NXV; ++c)
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) ab = fmaxf(ab, fabsf((float)xv[c][e]));
-  }
+    for (int e = 0; e < EPC; ++e) ab = fmaxf(ab, fabsf((float)xv[c][e]));
   float ar = 0.f, mn = 3.0e38f, mx = -3.0e38f;
   double y2 = 0.0;
 #pragma unroll
   for (int c = 0; c < NV4; ++c) {
     if (live(c)) {
       const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+      float y24 = 0.f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         ar = fmaxf(ar, fabsf(e4[e]));
         mn = fminf(mn, e4[e]);
         mx = fmaxf(mx, e4[e]);
-        y2 = fma((double)e4[e], (double)e4[e], y2);
+        y24 = fmaf(e4[e], e4[e], y24);
       }
+      y2 += (double)y24;
     }
   }
 #pragma unroll
@@ -794,42 +800,31 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
     const double pos = quant * (double)(d - 1);
     const int k = (int)floor(pos);
     const float frac = (float)(pos - (double)k);
-    unsigned prefix = 0u, mask = 0u;
-    int kk = k;
-#pragma unroll 1
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      hist[4 * lane] = 0u; hist[4 * lane + 1] = 0u; hist[4 * lane + 2] = 0u; hist[4 * lane + 3] = 0u;
+    // a_k = the value of rank k (0-based, ascending) among the |y| bit patterns: radix select in three rounds
+    // on bits 30..20, 19..9 and 8..0, each a histogram of up to 2048 bins kept by this wave in LDS.
+    auto clear_hist = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) *reinterpret_cast<uint4*>(hist + 256 * j + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      unsigned run_bin = 0xffffffffu, run_cnt = 0u;
+    };
+    // The bin that holds rank kk: lane l sums bins 32 l .. 32 l + 31 (its eight 16-byte pieces read in an order
+    // that depends on the lane number, which spreads them over the banks), a scan over the lanes finds the group,
+    // then lane i < 32 takes bin i of that group and a second scan finds the bin.
+    // -> bin, cum = entries in lower bins, cnt = entries in the bin; own / c2 / grp / idx stay for next_bin.
+    unsigned own = 0u, c2 = 0u;
+    int grp = 0, idx = 0;
+    auto pick = [&](unsigned kk, unsigned& bin, unsigned& cum, unsigned& cnt) __attribute__((always_inline)) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      own = 0u;
+      unsigned hb = (unsigned)lane * 128u + (unsigned)(lane & 7) * 16u;  // byte offset of piece (lane & 7) of this lane
+      asm volatile("" : "+v"(hb));  // recomputed here: eight piece addresses kept across the row cost registers
 #pragma unroll
-      for (int c = 0; c < NV4; ++c) {
-        const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
-        unsigned bin[4];
-        bool m[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const unsigned u = __float_as_uint(fabsf(e4[e]));
-          m[e] = live(c) && (u & mask) == prefix;
-          bin[e] = (u >> shift) & 255u;
-        }
-        // in the later rounds hardly any value still matches the prefix: skip the chunk for the whole wave
-        if (!__any((int)(m[0] | m[1] | m[2] | m[3]))) continue;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool same = m[e] && bin[e] == run_bin;
-          const bool change = m[e] && !same;
-          if (change && run_cnt) atomicAdd(const_cast<unsigned*>(&hist[run_bin]), run_cnt);
-          run_cnt = same ? run_cnt + 1u : (change ? 1u : run_cnt);
-          run_bin = change ? bin[e] : run_bin;
-        }
+      for (int j = 0; j < 8; ++j) {
+        const uint4 c = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(hist) + (hb ^ (unsigned)(j << 4)));
+        own += (c.x + c.y) + (c.z + c.w);
       }
-      if (run_cnt) atomicAdd(const_cast<unsigned*>(&hist[run_bin]), run_cnt);
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      // lane l owns bins 4l .. 4l+3; prefix scan over the lanes
-      const unsigned c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
-      const unsigned own = c0 + c1 + c2 + c3;
       unsigned incl = own;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
@@ -837,43 +832,108 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
         if (lane >= o) incl += up;
       }
       const unsigned excl = incl - own;
-      const bool hit = excl <= (unsigned)kk && (unsigned)kk < incl;  // exactly one lane (the counts sum to > kk)
-      unsigned cum = excl;
-      int bsel = 4 * lane;
-      if (cum + c0 <= (unsigned)kk) { cum += c0; ++bsel;
-        if (cum + c1 <= (unsigned)kk) { cum += c1; ++bsel;
-          if (cum + c2 <= (unsigned)kk) { cum += c2; ++bsel; } } }
-      const unsigned long long hits = __ballot(hit);
-      const int src = hits ? __builtin_ctzll(hits) : 0;
-      const unsigned sel_bin = (unsigned)__shfl(bsel, src);
-      const unsigned sel_cum = (unsigned)__shfl((int)cum, src);
-      prefix |= sel_bin << shift;
-      kk -= (int)sel_cum;
-      mask |= 255u << shift;
+      const unsigned long long hits = __ballot(excl <= kk && kk < incl);  // exactly one lane: the counts sum to > kk
+      grp = hits ? __builtin_ctzll(hits) : 0;
+      const unsigned base = (unsigned)__shfl((int)excl, grp);
+      c2 = lane < 32 ? hist[32 * grp + lane] : 0u;
+      unsigned incl2 = c2;
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {
+        const unsigned up = (unsigned)__shfl_up((int)incl2, o);
+        if (lane >= o) incl2 += up;
+      }
+      const unsigned excl2 = base + incl2 - c2;
+      const unsigned long long hits2 = __ballot(lane < 32 && excl2 <= kk && kk < excl2 + c2);
+      idx = hits2 ? __builtin_ctzll(hits2) : 0;
+      bin = (unsigned)(32 * grp + idx);
+      cum = (unsigned)__shfl((int)excl2, idx);
+      cnt = (unsigned)__shfl((int)c2, idx);
       __builtin_amdgcn_wave_barrier();
-    }
-    // prefix = bits of a_k; a_{k+1} = a_k if enough copies of it, else the smallest larger value
-    unsigned le = 0u, nxt = 0xffffffffu;
+    };
+    // first non-empty bin above the one pick() returned, 0xffffffff if there is none
+    auto next_bin = [&]() __attribute__((always_inline)) -> unsigned {
+      const unsigned long long nz = __ballot(lane < 32 && c2 > 0u) & ~((2ull << idx) - 1ull);
+      if (nz) return (unsigned)(32 * grp + __builtin_ctzll(nz));
+      const unsigned long long g = __ballot(own > 0u) & ~((2ull << grp) - 1ull);
+      if (!g) return 0xffffffffu;
+      const int g0 = __builtin_ctzll(g);
+      const unsigned c3 = lane < 32 ? hist[32 * g0 + lane] : 0u;
+      const unsigned long long nz3 = __ballot(c3 > 0u);
+      return (unsigned)(32 * g0 + __builtin_ctzll(nz3));
+    };
+    unsigned kk = (unsigned)k, bin, cum, cnt;
+    // round 1, bits 30..20: every value of the row counts
+    clear_hist();
 #pragma unroll
     for (int c = 0; c < NV4; ++c) {
       if (live(c)) {
         const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const unsigned u = __float_as_uint(fabsf(e4[e]));
-          if (u <= prefix) le += 1u;
-          else if (u < nxt) nxt = u;
-        }
+        for (int e = 0; e < 4; ++e) atomicAdd(&hist[(__float_as_uint(e4[e]) & 0x7fffffffu) >> 20], 1u);
       }
     }
+    pick(kk, bin, cum, cnt);
+    const unsigned p11 = bin;
+    kk -= cum;
+    // round 2, bits 19..9 of the values whose bits 30..20 equal p11
+    clear_hist();
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      le += (unsigned)__shfl_xor((int)le, o);
-      const unsigned w = (unsigned)__shfl_xor((int)nxt, o);
-      nxt = w < nxt ? w : nxt;
+    for (int c = 0; c < NV4; ++c) {
+      const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+      unsigned u[4];
+      bool m[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        u[e] = __float_as_uint(e4[e]) & 0x7fffffffu;
+        m[e] = live(c) && (u[e] >> 20) == p11;
+      }
+      if (!__any((int)(m[0] | m[1] | m[2] | m[3]))) continue;  // skipped by the whole wave
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (m[e]) atomicAdd(&hist[(u[e] >> 9) & 2047u], 1u);
+    }
+    pick(kk, bin, cum, cnt);
+    const unsigned p22 = (p11 << 11) | bin;
+    kk -= cum;
+    // round 3, bits 8..0 of the values whose bits 30..9 equal p22; the same pass finds the smallest value
+    // beyond that group: u - base wraps to >= 2^31 for every u < base = (p22 + 1) 2^9 <= 2^31
+    clear_hist();
+    const unsigned base = (p22 + 1u) << 9;
+    unsigned above = 0xffffffffu;
+#pragma unroll
+    for (int c = 0; c < NV4; ++c) {
+      const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+      unsigned u[4];
+      bool m[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        u[e] = __float_as_uint(e4[e]) & 0x7fffffffu;
+        m[e] = live(c) && (u[e] >> 9) == p22;
+        const unsigned w = u[e] - base;
+        above = w < above ? w : above;
+      }
+      if (!__any((int)(m[0] | m[1] | m[2] | m[3]))) continue;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (m[e]) atomicAdd(&hist[u[e] & 511u], 1u);
+    }
+    pick(kk, bin, cum, cnt);
+    kk -= cum;  // rank of a_k among its cnt copies
+    const unsigned prefix = (p22 << 9) | bin;
+    // a_{k+1} = a_k if another copy of it follows, else the smallest larger value: the next occupied bin of
+    // the last histogram, else the smallest value beyond the group
+    unsigned nxt = next_bin();
+    if (nxt != 0xffffffffu) nxt |= p22 << 9;
+    else {
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) {
+        const unsigned w = (unsigned)__shfl_xor((int)above, o);
+        above = w < above ? w : above;
+      }
+      if (above < 0x80000000u) nxt = above + base;
     }
     const float ak = __uint_as_float(prefix);
-    const float ak1 = ((int)le >= k + 2 || nxt == 0xffffffffu) ? ak : __uint_as_float(nxt);
+    const float ak1 = (cnt >= kk + 2u || nxt == 0xffffffffu) ? ak : __uint_as_float(nxt);
     float inc = __fmul_rn(frac, __fsub_rn(ak1, ak));
     asm volatile("" : "+v"(inc));  // keep the product rounded: no contraction with the add below
     t = __fadd_rn(ak, inc);
@@ -882,25 +942,26 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
   const float rs = ss > 0.f ? __fdiv_rn(1.0f, ss) : 0.f;
   const float sa = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
   const float ra = sa > 0.f ? __fdiv_rn(1.0f, sa) : 0.f;
-  const double ssd = (double)ss, sad = (double)sa, mnd = (double)mn;
+  const double sad = (double)sa, mnd = (double)mn;
   double es = 0.0, ea = 0.0;
 #pragma unroll
   for (int c = 0; c < NV4; ++c) {
     if (live(c)) {
       const float e4[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+      float es4 = 0.f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float val = e4[e];
-        const double vd = (double)val;
         float q = rintf(__fmul_rn(val, rs));
         q = __builtin_amdgcn_fmed3f(q, -7.f, 7.f);
-        const double dsym = fma(-(double)q, ssd, vd);
-        es = fma(dsym, dsym, es);
+        const float dsym = fmaf(-q, ss, val);
+        es4 = fmaf(dsym, dsym, es4);
         float qa = rintf(__fmul_rn(__fsub_rn(val, mn), ra));
         qa = __builtin_amdgcn_fmed3f(qa, 0.f, 15.f);
-        const double dasy = vd - fma((double)qa, sad, mnd);
+        const double dasy = (double)val - fma((double)qa, sad, mnd);
         ea = fma(dasy, dasy, ea);
       }
+      es += (double)es4;
     }
   }
 #pragma unroll
