@@ -149,21 +149,55 @@ struct EpiStore : EpiBase {
   int64_t ldc, batch_stride, split_stride;
   int M, N;
   float alpha = 1.f;  // C = alpha * acc
+  // An accumulator block leaves the matrix pipe with one COLUMN per lane (4 consecutive rows in 4 registers), so
+  // a direct store is a 4-byte store per lane, 256 of them per wave and tile, and the address path handles
+  // each at the same rate as a 16-byte one.  Here every 8 x 32 piece (4 registers of the two wave halves)
+  // passes through a 1.1 KiB buffer of the wave's own in LDS and comes back as 16 bytes per lane, 8 lanes
+  // to a 128-byte row piece: 64 stores per wave and tile, each of 8 whole 128-byte lines.
+  static constexpr int kPieceWords = 8 * 32 + 32;  // rows 4..7 sit 32 words further: the two halves hit different banks
+  static constexpr int kPieceBufs = 4;
+  static_assert(TL::NT / 64 * kPieceBufs * kPieceWords * 4 <= TL::LDS_BYTES, "piece buffers must fit the operand LDS");
   __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int,
                                              int, int ks, int m0, int n0) const {
     const Frag<TL> f;
     float* base = C + (int64_t)ks * split_stride + (int64_t)batch * batch_stride;
+    // 16-byte stores need aligned rows and whole groups of 4 columns inside N (uniform over the launch)
+    const bool vec = ((reinterpret_cast<uintptr_t>(base) | (uintptr_t)(ldc * 4)) & 15) == 0 && (N & 3) == 0;
+    if (!vec) {
+#pragma unroll
+      for (int mb = 0; mb < TL::MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < TL::NB; ++nb) {
+          const int n = n0 + f.n_of(nb);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = m0 + f.m_of(mb, r);
+            if (m < M && n < N) base[(int64_t)m * ldc + n] = alpha * acc[mb][nb][r];
+          }
+        }
+      return;
+    }
+    extern __shared__ __align__(16) char lds_raw[];
+    __syncthreads();  // every wave has read its last operand slab: the LDS is free
+    float* buf = reinterpret_cast<float*>(lds_raw) + (threadIdx.x >> 6) * (kPieceBufs * kPieceWords);
+    const int wofs = f.half * 160 + (f.lane & 31);  // register i of this lane -> row 4 half + i, column lane % 32
+    const int rrow = f.lane >> 3, rcol = 4 * (f.lane & 7);
+    const int rofs = rrow * 32 + (rrow >> 2) * 32 + rcol;
 #pragma unroll
     for (int mb = 0; mb < TL::MB; ++mb)
 #pragma unroll
-      for (int nb = 0; nb < TL::NB; ++nb) {
-        const int n = n0 + f.n_of(nb);
+      for (int nb = 0; nb < TL::NB; ++nb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + f.m_of(mb, r);
-          if (m < M && n < N) base[(int64_t)m * ldc + n] = alpha * acc[mb][nb][r];
+        for (int g = 0; g < 4; ++g) {
+          float* b = buf + (((mb * TL::NB + nb) * 4 + g) % kPieceBufs) * kPieceWords;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) b[wofs + 32 * i] = alpha * acc[mb][nb][4 * g + i];
+          // the wave's LDS operations complete in order: no barrier between its own writes and reads
+          const float4 v = *reinterpret_cast<const float4*>(b + rofs);
+          const int m = m0 + f.m_block(mb) + 8 * g + rrow;
+          const int n = n0 + f.wn * TL::WTN + nb * 32 + rcol;
+          if (m < M && n < N) *reinterpret_cast<float4*>(base + (int64_t)m * ldc + n) = v;
         }
-      }
   }
 };
 
