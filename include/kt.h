@@ -56,7 +56,8 @@ enum {
 typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
 typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3,
                KT_OP_QUANT_METRICS = 4, KT_OP_FUSE_ROTATION = 5,
-               KT_OP_SENSITIVITY = 6 } kt_op;
+               KT_OP_SENSITIVITY = 6, KT_OP_LOSS_GRAD_RECOMPUTE = 7,
+               KT_OP_POOLED_LOSS_GRAD_RECOMPUTE = 8 } kt_op;
 
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
@@ -71,7 +72,9 @@ const char* kt_build_id(void);
 const char* kt_last_error(void);
 
 /* Scratch bytes the given operation needs for these sizes (0 on bad sizes).
- * For KT_OP_CAYLEY `n` is ignored.  Host call, launches nothing. */
+ * For KT_OP_CAYLEY `n` is ignored.  KT_OP_LOSS_GRAD / KT_OP_POOLED_LOSS_GRAD: the recommended size
+ * (with room to keep Y, see kt_kurtosis_loss_grad); KT_OP_LOSS_GRAD_RECOMPUTE /
+ * KT_OP_POOLED_LOSS_GRAD_RECOMPUTE: the least those entry points accept.  Host call, launches nothing. */
 size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtype x_dtype);
 
 /*
@@ -86,10 +89,14 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
  *   dL/dy_ij = s_i 4/(n d m2_i^2) [c_ij^3 - m3_i - kappa_i m2_i c_ij],  s_i = f'(kappa_i)
  *   dR = X^T (dL/dY)
  *
- * Y and dL/dY as such never reach HBM in row-major form: Y is consumed in the GEMM
- * epilogue (row moments), recomputed for the backward pass, and dL/dY is kept only
- * as the token-minor scratch operand of the last GEMM (which reads X itself in place when
- * X is bf16 and d a multiple of 256, through a token-minor copy otherwise).
+ * Y is consumed in the forward GEMM's epilogue (row moments).  For the backward pass it is either
+ * KEPT by that epilogue (fp32, token-minor, 4 n d bytes of workspace per problem) and dL/dY computed
+ * from it entry by entry, or RECOMPUTED by a second GEMM whose epilogue forms dL/dY: the first when
+ * the workspace handed in has the room (kt_workspace_bytes(KT_OP_LOSS_GRAD) asks for it while Y is at
+ * most 64 GiB), the second otherwise (KT_OP_LOSS_GRAD_RECOMPUTE is the smaller size).  Both give the
+ * same bits: dL/dY comes from the same fp32 accumulators through the same arithmetic.  dL/dY exists
+ * only as the token-minor scratch operand of the last GEMM (which reads X itself in place when X is
+ * bf16 and d a multiple of 256, through a token-minor copy otherwise).
  *
  *  X        [batch][n][ldx] row-major, x_dtype (KT_BF16, or KT_F32 for the fp32 path);
  *           d <= ldx <= 2^22, rows 16-byte aligned (ldx % 8 == 0 for bf16, % 4 for fp32).
@@ -125,7 +132,7 @@ kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64
  * Arguments as for kt_kurtosis_loss_grad; `kappa` [batch] fp32 or NULL receives kappa.
  * Three passes over X (moments, recompute + dL/dY, X^T G) for every d, d = 128 included:
  * the gradient needs the pooled statistics of the whole problem first.
- * Workspace: kt_workspace_bytes(KT_OP_POOLED_LOSS_GRAD, ...).
+ * Workspace: kt_workspace_bytes(KT_OP_POOLED_LOSS_GRAD, ...) (Y kept) or (KT_OP_POOLED_LOSS_GRAD_RECOMPUTE, ...).
  */
 kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64_t ldr,
                                        int64_t batch, int64_t n, int64_t d,

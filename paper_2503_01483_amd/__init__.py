@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     KT_OP_QUANT_METRICS,
     KT_OP_FUSE_ROTATION,
     KT_OP_SENSITIVITY,
+    KT_OP_LOSS_GRAD_RECOMPUTE,
+    KT_OP_POOLED_LOSS_GRAD_RECOMPUTE,
     KtError,
     lib,
     lib_path,

@@ -10,7 +10,7 @@ _lib = None
 
 KT_F32, KT_BF16 = 0, 1
 KT_OP_LOSS_GRAD, KT_OP_CAYLEY, KT_OP_FAKEQUANT, KT_OP_POOLED_LOSS_GRAD, KT_OP_QUANT_METRICS = 0, 1, 2, 3, 4
-KT_OP_FUSE_ROTATION, KT_OP_SENSITIVITY = 5, 6
+KT_OP_FUSE_ROTATION, KT_OP_SENSITIVITY, KT_OP_LOSS_GRAD_RECOMPUTE, KT_OP_POOLED_LOSS_GRAD_RECOMPUTE = 5, 6, 7, 8
 
 EXPORTS = ("kt_version", "kt_last_error", "kt_workspace_bytes", "kt_kurtosis_loss_grad",
            "kt_pooled_kurtosis_loss_grad", "kt_cayley_step", "kt_cayley_adam_step", "kt_rotate_fakequant_int4", "kt_rotate_quant_metrics", "kt_hadamard_rows", "kt_fuse_rotation", "kt_quant_sensitivity", "kt_profile_enable", "kt_profile_read",
@@ -160,32 +160,38 @@ def _xr_dims(X, R):
 
 
 def kt_kurtosis_loss_grad(X, R, *, kappa_target=0.0, loss=None, row_kurt=None, dR=None,
-                          workspace=None, stream=None):
-    """loss [batch] fp32 (returned), optional row_kurt [batch][n] and dR [batch][d][d] outputs."""
+                          workspace=None, stream=None, recompute=False):
+    """loss [batch] fp32 (returned), optional row_kurt [batch][n] and dR [batch][d][d] outputs.
+    recompute=True hands the library only the smaller workspace, with which it recomputes Y for the
+    backward pass instead of keeping it (same result)."""
     X, R, batch, n, d = _xr_dims(X, R)
     if loss is None:
         loss = torch.empty(batch, dtype=torch.float32, device=X.device)
     xdt = _dtype_code(X)
-    need = kt_workspace_bytes(KT_OP_LOSS_GRAD, batch, n, d, xdt)
+    need = kt_workspace_bytes(KT_OP_LOSS_GRAD_RECOMPUTE if recompute else KT_OP_LOSS_GRAD, batch, n, d, xdt)
     ws = (workspace or Workspace(X.device)).get(need)
     _check(lib().kt_kurtosis_loss_grad(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
                                        _dtype_code(R), float(kappa_target), _ptr(loss),
-                                       _ptr(row_kurt), _ptr(dR), _ptr(ws), ws.numel(), _stream(stream)))
+                                       _ptr(row_kurt), _ptr(dR), _ptr(ws), need if recompute else ws.numel(),
+                                       _stream(stream)))
     return loss
 
 
 def kt_pooled_kurtosis_loss_grad(X, R, *, kappa_target=1.8, rms_eps=0.0, loss=None, kappa=None, dR=None,
-                                 workspace=None, stream=None):
-    """Paper-literal pooled loss [batch] fp32 (returned), optional kappa [batch] and dR outputs."""
+                                 workspace=None, stream=None, recompute=False):
+    """Paper-literal pooled loss [batch] fp32 (returned), optional kappa [batch] and dR outputs.
+    recompute: as for kt_kurtosis_loss_grad."""
     X, R, batch, n, d = _xr_dims(X, R)
     if loss is None:
         loss = torch.empty(batch, dtype=torch.float32, device=X.device)
     xdt = _dtype_code(X)
-    need = kt_workspace_bytes(KT_OP_POOLED_LOSS_GRAD, batch, n, d, xdt)
+    need = kt_workspace_bytes(KT_OP_POOLED_LOSS_GRAD_RECOMPUTE if recompute else KT_OP_POOLED_LOSS_GRAD,
+                              batch, n, d, xdt)
     ws = (workspace or Workspace(X.device)).get(need)
     _check(lib().kt_pooled_kurtosis_loss_grad(_ptr(X), X.stride(1), _ptr(R), R.stride(1), batch, n, d, xdt,
                                               _dtype_code(R), float(kappa_target), float(rms_eps), _ptr(loss),
-                                              _ptr(kappa), _ptr(dR), _ptr(ws), ws.numel(), _stream(stream)))
+                                              _ptr(kappa), _ptr(dR), _ptr(ws), need if recompute else ws.numel(),
+                                              _stream(stream)))
     return loss
 
 

@@ -206,12 +206,20 @@ struct LossGradPlan {
   int P;           // moment partials per token
   int tiles_dd;    // tiles of the d x d output GEMM
   int slabs_per_split, split_k;
-  size_t o_rt, o_part, o_coef, o_losspart, o_xt, o_gt, o_splitk, o_gstat, total;
+  size_t o_rt, o_part, o_coef, o_losspart, o_xt, o_gt, o_splitk, o_gstat, o_yt, total;
   int loss_blocks;
+  bool keep_y;     // the forward pass writes Y (fp32, token-minor) and the backward pass reads it instead of recomputing it
 };
 
-static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype xdt, bool pooled = false) {
+// Up to this many bytes of kept Y, kt_workspace_bytes(KT_OP_LOSS_GRAD / KT_OP_POOLED_LOSS_GRAD) asks for the
+// room to keep it (4 n d bytes per problem); beyond, for the recompute form.
+constexpr int64_t kKeepYMaxBytes = (int64_t)64 << 30;
+
+static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype xdt, bool pooled = false,
+                                   bool keep_y = false) {
   LossGradPlan p;
+  p.keep_y = false;
+  p.o_yt = 0;
   p.fp32 = (xdt == KT_F32);
   p.esz = p.fp32 ? 4 : 2;
   p.fused = !p.fp32 && d == 128 && !pooled;  // the pooled loss needs its global statistics before the gradient
@@ -261,8 +269,16 @@ static LossGradPlan plan_loss_grad(int64_t batch, int64_t n, int64_t d, kt_dtype
   p.o_xt = c.take(big_tiles ? 0 : (size_t)batch * d * p.nblk * p.tb * p.esz);  // big tiles read X as it is
   p.o_gt = c.take((size_t)batch * d * p.nblk * p.tb * p.esz);
   p.o_splitk = c.take(p.split_k > 1 ? (size_t)p.split_k * batch * d * d * 4 : 0);
+  p.keep_y = keep_y;
+  p.o_yt = c.take(keep_y ? (size_t)batch * d * p.nblk * p.tb * 4 : 0);
   p.total = c.off;
   return p;
+}
+
+// The plan kt_workspace_bytes recommends: Y kept when it is small enough and the path has a backward GEMM to save.
+static bool keep_y_recommended(int64_t batch, int64_t n, int64_t d, kt_dtype xdt, bool pooled) {
+  if (xdt == KT_BF16 && d == 128 && !pooled) return false;  // single-pass kernel
+  return batch * round_up(n, 128) * d * 4 <= kKeepYMaxBytes;
 }
 
 struct CayleyPlan {
@@ -417,13 +433,22 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
   // a0: R -> R^T in the GEMM dtype
   if (!prep_rt<T>(R, ldr, rdt, RT, batch, d, st)) return fail(KT_ERR_DEVICE, "prep_rt launch failed");
 
-  // a1: forward GEMM (features on m, tokens on n) with the moment epilogue
+  // a1: forward GEMM (features on m, tokens on n) with the moment epilogue; with keep_y it also writes Y
+  const bool keep = p.keep_y && dR;
+  float* YT = reinterpret_cast<float*>(ws + p.o_yt);
   {
     ProfScope prof(0, st);
     EpiMoments<TFWD> e;
     e.part = part; e.n_tokens = (int)n; e.d = (int)d; e.P = p.P;
-    if (!launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st))
-      return fail(KT_ERR_DEVICE, "forward GEMM launch failed");
+    bool ok;
+    if (keep) {
+      EpiMomentsKeep<TFWD> ek;
+      ek.mom = e; ek.YT = YT; ek.ldt = p.ldt; ek.tb = p.tb; ek.batch_stride = d * p.nblk * p.tb;
+      ok = launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, ek, st);
+    } else {
+      ok = launch_gemm<TFWD>(RT, d, d * d, (int)d, Xp, ldx, n * ldx, (int)n, d, 0, (int)batch, e, st);
+    }
+    if (!ok) return fail(KT_ERR_DEVICE, "forward GEMM launch failed");
   }
   if (pooled) {
     // a2, pooled form: pooled sums -> global statistics and loss -> per-token coefficients
@@ -465,8 +490,15 @@ static kt_status run_loss_grad(const LossGradPlan& p, const void* X, int64_t ldx
     }
     if (!launch_ok()) return fail(KT_ERR_DEVICE, "X transpose launch failed");
   }
-  // a3: recompute Y, write dL/dY token-minor
-  {
+  // a3: dL/dY token-minor, from the kept Y entry by entry or from a recomputed Y in the GEMM epilogue
+  if (keep) {
+    ProfScope prof(1, st);
+    constexpr int kFeats = 8;
+    dim3 grid((unsigned)ceil_div(p.ldt, 256), (unsigned)ceil_div(d, 4 * kFeats), (unsigned)batch);
+    hipLaunchKernelGGL((grad_from_y_kernel<T, kFeats>), grid, dim3(256), 0, st, YT, coef, GT, p.ldt, p.tb,
+                       d * p.nblk * p.tb, (int)n, (int)d);
+    if (!launch_ok()) return fail(KT_ERR_DEVICE, "gradient kernel launch failed");
+  } else {
     ProfScope prof(1, st);
     EpiGrad<TFWD> e;
     e.coef = coef; e.GT = GT; e.ldt = p.ldt; e.tb = p.tb; e.batch_stride = d * p.nblk * p.tb;
@@ -881,8 +913,14 @@ size_t kt_workspace_bytes(kt_op op, int64_t batch, int64_t n, int64_t d, kt_dtyp
   switch (op) {
     case KT_OP_LOSS_GRAD:
       if (n < 1) return 0;
+      return plan_loss_grad(batch, n, d, x_dtype, false, keep_y_recommended(batch, n, d, x_dtype, false)).total;
+    case KT_OP_LOSS_GRAD_RECOMPUTE:
+      if (n < 1) return 0;
       return plan_loss_grad(batch, n, d, x_dtype).total;
     case KT_OP_POOLED_LOSS_GRAD:
+      if (n < 1) return 0;
+      return plan_loss_grad(batch, n, d, x_dtype, true, keep_y_recommended(batch, n, d, x_dtype, true)).total;
+    case KT_OP_POOLED_LOSS_GRAD_RECOMPUTE:
       if (n < 1) return 0;
       return plan_loss_grad(batch, n, d, x_dtype, true).total;
     case KT_OP_QUANT_METRICS:
@@ -916,9 +954,13 @@ kt_status kt_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R, int64
   if (s != KT_OK) return s;
   if (!loss) return fail(KT_ERR_INVALID_ARG, "loss must not be null");
   if (!(kappa_target >= 0.f)) return fail(KT_ERR_INVALID_ARG, "kappa_target must be >= 0");
-  const LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype);
+  LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype);
   s = check_ws(workspace, workspace_bytes, p.total);
   if (s != KT_OK) return s;
+  if (!p.fused && dR) {  // room for Y: keep it instead of recomputing it (same result)
+    const LossGradPlan pk = plan_loss_grad(batch, n, d, x_dtype, false, true);
+    if (workspace_bytes >= pk.total) p = pk;
+  }
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (p.fused)
@@ -945,9 +987,13 @@ kt_status kt_pooled_kurtosis_loss_grad(const void* X, int64_t ldx, const void* R
   if (!loss) return fail(KT_ERR_INVALID_ARG, "loss must not be null");
   if (!(kappa_target >= 0.f)) return fail(KT_ERR_INVALID_ARG, "kappa_target must be >= 0");
   if (!(rms_eps >= 0.f)) return fail(KT_ERR_INVALID_ARG, "rms_eps must be >= 0");
-  const LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype, true);
+  LossGradPlan p = plan_loss_grad(batch, n, d, x_dtype, true);
   s = check_ws(workspace, workspace_bytes, p.total);
   if (s != KT_OK) return s;
+  if (dR) {
+    const LossGradPlan pk = plan_loss_grad(batch, n, d, x_dtype, true, true);
+    if (workspace_bytes >= pk.total) p = pk;
+  }
   char* ws = static_cast<char*>(workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   PooledArgs pa;

@@ -194,6 +194,51 @@ __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __res
   if (threadIdx.x == 0) loss_part[(int64_t)batch * gridDim.x + blockIdx.x] = s;
 }
 
+// dL/dY from a kept Y: GT[i] = grad_value(YT[i], coef of i's token) for every entry of the token-minor
+// layout that EpiMomentsKeep / EpiGrad write (rows = features, blocks of tb tokens, tokens permuted inside
+// groups of 128: position 4 j + k of a group holds token j + 32 k).  A half wave takes one group of 128
+// positions (16 bytes of YT per lane), its four tokens' coefficients stay in registers while it walks
+// FEATS feature rows; the four waves of a workgroup take four runs of feature rows of the same two groups.
+// grid = (ceil(ldt / 256), ceil(d / (4 FEATS)), batch).  Padding tokens (>= n) get alpha = 0, as in EpiGrad.
+template <typename T, int FEATS>
+__global__ __launch_bounds__(256) void grad_from_y_kernel(const float* __restrict__ YT,
+                                                          const floatx4* __restrict__ coef, T* __restrict__ GT,
+                                                          int64_t ldt, int64_t tb, int64_t batch_stride, int n,
+                                                          int d) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, batch = blockIdx.z;
+  const int64_t group0 = ((int64_t)blockIdx.x * 2 + (lane >> 5)) * 128;
+  if (group0 >= ldt) return;  // ldt is a multiple of 128: the second half wave of the last workgroup may have no group
+  const int j = lane & 31;
+  float alpha[4], mu[4], beta[4], m3[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int64_t token = group0 + j + 32 * k;
+    floatx4 c4 = {0.f, 0.f, 0.f, 0.f};
+    if (token < n) c4 = coef[(int64_t)batch * n + token];
+    alpha[k] = c4[0]; mu[k] = c4[1]; beta[k] = c4[2]; m3[k] = c4[3];
+  }
+  const int64_t pos0 = group0 + 4 * j;
+  const int64_t blk = pos0 / tb;
+  const int64_t base = (int64_t)batch * batch_stride + blk * d * tb + (pos0 - blk * tb);
+  const int f0 = (blockIdx.y * 4 + wave) * FEATS;
+  float4 y[FEATS];
+#pragma unroll
+  for (int i = 0; i < FEATS; ++i)
+    if (f0 + i < d) y[i] = *reinterpret_cast<const float4*>(YT + base + (int64_t)(f0 + i) * tb);
+#pragma unroll
+  for (int i = 0; i < FEATS; ++i) {
+    if (f0 + i < d) {
+      typedef T vecT __attribute__((ext_vector_type(4)));
+      vecT v;
+      v[0] = from_float<T>(grad_value(y[i].x, alpha[0], mu[0], beta[0], m3[0]));
+      v[1] = from_float<T>(grad_value(y[i].y, alpha[1], mu[1], beta[1], m3[1]));
+      v[2] = from_float<T>(grad_value(y[i].z, alpha[2], mu[2], beta[2], m3[2]));
+      v[3] = from_float<T>(grad_value(y[i].w, alpha[3], mu[3], beta[3], m3[3]));
+      *reinterpret_cast<vecT*>(GT + base + (int64_t)(f0 + i) * tb) = v;
+    }
+  }
+}
+
 // ---- pooled (paper-literal) loss: kurtosis of ALL entries of RMSNorm(X R) as one sample ------
 // Row sums of z^k = (y / rho)^k follow from the row's sums of y^k, so the forward GEMM with the
 // moment epilogue is used unchanged.  Stage 1: per token rho and the block partials of the four

@@ -93,6 +93,14 @@ __host__ __device__ __forceinline__ int64_t token_position(int64_t t) {
   return (t & ~(int64_t)127) + ((t & 31) << 2) + ((t & 127) >> 5);
 }
 
+// dL/dy of one entry from the row's coefficients {alpha, mu, beta, m3}; alpha = 0 (padding tokens, rows
+// without spread) gives 0 by itself as long as y is finite.  One definition for the recompute epilogue and
+// for the kernel that reads a kept Y, so that the two paths round alike.
+__device__ __forceinline__ float grad_value(float y, float alpha, float mu, float beta, float m3) {
+  const float c = y - mu;
+  return alpha * fmaf(c, fmaf(c, c, -beta), -m3);
+}
+
 template <class TL>
 struct EpiGrad : EpiBase {
   using T = typename TL::T;
@@ -127,14 +135,47 @@ struct EpiGrad : EpiBase {
         for (int r = 0; r < 16; ++r) {
           vecT v;
 #pragma unroll
-          for (int nb = 0; nb < TL::NB; ++nb) {
-            const float c = acc[mb][nb][r] - mu[nb];
-            // alpha = 0 (padding tokens, rows without spread) gives 0 by itself: the accumulators of padding
-            // tokens come from re-read valid rows and are finite
-            v[nb] = from_float<T>(alpha[nb] * fmaf(c, fmaf(c, c, -beta[nb]), -m3[nb]));
-          }
+          for (int nb = 0; nb < TL::NB; ++nb)  // (the accumulators of padding tokens come from re-read valid rows and are finite)
+            v[nb] = from_float<T>(grad_value(acc[mb][nb][r], alpha[nb], mu[nb], beta[nb], m3[nb]));
           const int feat = m0 + f.m_of(mb, r);
           *reinterpret_cast<vecT*>(out + (int64_t)feat * tb) = v;
+        }
+      }
+    }
+  }
+};
+
+// ---- forward pass that also keeps Y: the moments of EpiMoments, and the fp32 accumulators written
+// in the layout of GT above (features on the rows, tokens permuted inside groups of 128, blocks of tb
+// tokens): one 16-byte store per lane and feature.  grad_from_y_kernel then turns YT into GT entry by
+// entry, which replaces the recompute GEMM of the backward pass (same accumulators, same arithmetic: the
+// gradient is bit-identical) at the price of n d 4 bytes of scratch, one write and one read of them.
+template <class TL>
+struct EpiMomentsKeep : EpiBase {
+  EpiMoments<TL> mom;
+  float* YT;
+  int64_t ldt, tb, batch_stride;  // batch_stride in elements of YT
+  static_assert(TL::BN % 128 == 0 && (TL::WTN == 128 || TL::WTN == 64), "token groups are 128 wide");
+  __device__ __forceinline__ void operator()(floatx16 (&acc)[TL::MB][TL::NB], int batch, int tm,
+                                             int tn, int ks, int m0, int n0) const {
+    mom(acc, batch, tm, tn, ks, m0, n0);
+    typedef float vecF __attribute__((ext_vector_type(TL::NB)));
+    const Frag<TL> f;
+    const int wave_tok0 = n0 + f.wn * TL::WTN;
+    const int group0 = wave_tok0 & ~127;
+    if (group0 >= ldt) return;
+    const int64_t pos0 = group0 + ((f.lane & 31) << 2) + ((wave_tok0 & 127) >> 5);
+    const int64_t blk = pos0 / tb;
+    float* out = YT + (int64_t)batch * batch_stride + blk * mom.d * tb + (pos0 - blk * tb);
+#pragma unroll
+    for (int mb = 0; mb < TL::MB; ++mb) {
+      if (m0 + f.m_block(mb) < mom.d) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          vecF v;
+#pragma unroll
+          for (int nb = 0; nb < TL::NB; ++nb) v[nb] = acc[mb][nb][r];
+          *reinterpret_cast<vecF*>(out + (int64_t)(m0 + f.m_of(mb, r)) * tb) = v;
         }
       }
     }

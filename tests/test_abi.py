@@ -34,8 +34,12 @@ def test_version_and_error_text():
 def test_workspace_bytes():
     f = kt.kt_workspace_bytes
     assert f(kt.KT_OP_LOSS_GRAD, 1, 2048, 256, kt.KT_F32) > 2 * 2048 * 256 * 4
+    small = f(kt.KT_OP_LOSS_GRAD_RECOMPUTE, 1, 131072, 4096, kt.KT_BF16)
+    assert 2**30 < small < 1.25 * 2**30         # the token-minor dL/dY dominates (X is read in place)
     big = f(kt.KT_OP_LOSS_GRAD, 1, 131072, 4096, kt.KT_BF16)
-    assert 2**30 < big < 1.25 * 2**30           # the token-minor dL/dY dominates (X is read in place)
+    assert big - small == 131072 * 4096 * 4     # plus Y kept in fp32
+    assert f(kt.KT_OP_POOLED_LOSS_GRAD, 1, 4096, 512, kt.KT_BF16) - \
+        f(kt.KT_OP_POOLED_LOSS_GRAD_RECOMPUTE, 1, 4096, 512, kt.KT_BF16) == 4096 * 512 * 4
     assert f(kt.KT_OP_LOSS_GRAD, 1, 100, 100, kt.KT_BF16) == 0   # d not a multiple of 128
     assert f(kt.KT_OP_LOSS_GRAD, 0, 100, 128, kt.KT_BF16) == 0
     assert f(kt.KT_OP_CAYLEY, 1, 0, 4096, kt.KT_F32) >= 5 * 4096 * 4096 * 4
