@@ -86,7 +86,7 @@ class ClockSampler:
                 "source": "sysfs pp_dpm_sclk / hwmon power1_input polled by a host thread during the timed steps"}
 
 
-def phase_stamps(kt, step, d, n):
+def phase_stamps(kt, step, d, n, recompute):
     """One step with the GEMM kernel's own time stamps (wave 0 of every workgroup: shader-clock counter at entry,
     after the prologue, after the main loop, after the epilogue; the 100 MHz counter at entry and exit)."""
     import ctypes
@@ -101,8 +101,10 @@ def phase_stamps(kt, step, d, n):
     L.kt_debug_stamps_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
     assert L.kt_debug_stamps_read(buf.ctypes.data_as(ctypes.c_void_p), buf.nbytes) == 0
     r_all = buf.reshape(slots, wgs, words).astype(np.int64)
-    names = ["forward + row moments", "recompute + dL/dY", "dR = X^T G", "Cayley: M = dR R^T", "Cayley iteration 1",
-             "Cayley iteration 2", "Cayley iteration 3", "Cayley iteration 4"]
+    cay = ["Cayley: M = dR R^T"] + [f"Cayley iteration {i}" for i in range(1, 7)]
+    names = (["forward + row moments", "recompute + dL/dY", "dR = X^T G"] if recompute else
+             ["forward + row moments + Y kept", "dR = X^T G"]) + cay   # the GEMM launches of a step, in order
+    k_of = ([d, d, n] if recompute else [d, n])                          # contraction length of the big ones
     out = []
     for s in range(slots):
         r = r_all[s][r_all[s][:, 3] > 0]
@@ -117,8 +119,8 @@ def phase_stamps(kt, step, d, n):
                "cycles_per_workgroup_median": {"prologue": int(np.median(pro)), "main_loop": int(np.median(loop)), "epilogue": int(np.median(epi))},
                "shader_clock_mhz_median": round(float(np.median(tot / np.maximum(wall_us, 1e-9))), 0),
                "cu_occupancy_of_span": round(float(wall_us.sum() / (span_us * 256)), 4)}
-        if s < 3:  # K slabs x 64 matrix instructions per wave x 32 cycles each, back to back
-            k = d if s < 2 else n
+        if s < len(k_of):  # K slabs x 64 matrix instructions per wave x 32 cycles each, back to back
+            k = k_of[s]
             rec["main_loop_efficiency"] = round(float((k / 64) * 64 * 32 / np.median(loop)), 4)
         out.append(rec)
     print(json.dumps({"phase_stamps": out}))
@@ -245,7 +247,7 @@ def main():
         step()
     torch.cuda.synchronize()
     if args.phase_stamps:
-        phase_stamps(kt, step, d, n)
+        phase_stamps(kt, step, d, n, args.recompute)
         return
     loss_first = loss.clone()
     kt.kt_profile_enable(8 * args.steps + 8)
