@@ -166,11 +166,11 @@ def test_c5_size_cayley_step_against_a_double_precision_solve():
 
 
 def test_c3_full_size_pooled_loss():
-    """The paper-literal pooled loss at C3 size.  The CPU oracle cannot rotate 131072 x 4096 in test
-    time; the pooled kurtosis of the definition is evaluated in fp64 by the framework's matmul on the
-    device instead (an independent library routine on the same bf16 values), the gradient by the
-    invariants the RMSNorm forces (every row of dL/dY is orthogonal to y, so <dR, R> = 0) and by
-    a row chunk against the oracle."""
+    """The paper-literal pooled loss at C3 size.  The comparison with the ORACLE is the 512-row chunk at the end
+    (at the real d).  SECONDARY to it, because the CPU oracle cannot rotate 131072 x 4096 in test time: the
+    pooled kurtosis of the definition evaluated in fp64 by the framework's matmul on the device (an independent
+    library routine on the same bf16 values), and the invariants the RMSNorm forces on the gradient (every row
+    of dL/dY is orthogonal to y, so <dR, R> = 0)."""
     X, R, cfg = ktgen.make_problem("C3", seed=0, device="cuda")
     b, n, d = X.shape
     ws = kt.Workspace()

@@ -1,4 +1,6 @@
-"""The multi-step protocol of the d = 2048 configuration as it is stated (R0 = identity, ten consecutive
+"""The multi-step protocols of the d = 2048 and d = 8192 configurations as sequences.
+
+The d = 2048 configuration as it is stated (R0 = identity, ten consecutive
 loss + gradient + Cayley steps, lr = 1e-2, bf16 activations with 16 outlier channels x100 and 5 % Student-t
 entries), on a row chunk the oracle can do, teacher-forced: at every step the GPU starts from the ORACLE's
 rotation of that step, so that the two cannot drift apart and each step's outputs can be held to the path
@@ -59,3 +61,34 @@ def test_c2_protocol_ten_steps_from_the_identity_teacher_forced():
     RtR = Ro.T @ Ro
     # the chain passes through fp32 at every step (the rotation both sides start from): each rounding adds ~1e-7
     assert np.abs(RtR - np.eye(d)).max() < 1e-6
+
+
+def test_c5_protocol_twenty_steps_free_running_stay_orthogonal_and_descend():
+    """The twenty optimiser steps of the d = 8192 configuration as a SEQUENCE on the device (its recipe: bf16
+    activations, 64 outlier channels x200, 5 % Student-t entries, random orthogonal start, lr = 1e-2), on 4096 token
+    rows.  At this size the oracle's retraction takes a minute per step, so the sequence is held to what is true of
+    any correct sequence: every step is accepted, R stays orthogonal (each retraction is a Cayley transform of a
+    skew matrix: errors only add up, a few 1e-8 per step), and the kurtosis loss falls.  A single step at this size
+    is compared element by element in test_gpu_fullsize.py."""
+    steps = 20
+    X, R, cfg = ktgen.make_problem("C5", seed=0, n=4096, device="cuda")
+    d, lr = cfg["d"], cfg["lr"]
+    assert d == 8192 and cfg["steps"] == steps
+    ws = kt.Workspace()
+    Rw = R.clone()
+    dR = torch.empty_like(Rw)
+    infos = torch.zeros((steps, 1), dtype=torch.int32, device="cuda")
+    losses = torch.zeros((steps, 1), device="cuda")
+    oe = torch.zeros(1, device="cuda")
+    for k in range(steps):
+        kt.kt_kurtosis_loss_grad(X, Rw, loss=losses[k], dR=dR, workspace=ws)
+        kt.kt_cayley_step(Rw, dR, lr, ortho_err=oe if k == steps - 1 else None, info=infos[k], workspace=ws)
+    torch.cuda.synchronize()
+    assert bool((infos > 0).all()), infos.flatten().tolist()
+    L = losses.flatten().tolist()
+    assert all(np.isfinite(L)) and L[-1] < L[0] - 1e-3, L       # (a random rotation already spreads the outliers: 3.000 -> 2.986)
+    assert all(b < a for a, b in zip(L, L[1:])), L               # lr = 1e-2: a descent step every time
+    assert oe.item() < 2e-6, oe.item()
+    Rd = Rw[0].double()
+    err = float((Rd.T @ Rd - torch.eye(d, dtype=torch.float64, device="cuda")).abs().max())
+    assert err < 2e-6, err
