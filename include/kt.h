@@ -53,11 +53,15 @@ enum {
   KT_ERR_NOT_SUPPORTED = 6
 };
 
-typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
-typedef enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3,
-               KT_OP_QUANT_METRICS = 4, KT_OP_FUSE_ROTATION = 5,
-               KT_OP_SENSITIVITY = 6, KT_OP_LOSS_GRAD_RECOMPUTE = 7,
-               KT_OP_POOLED_LOSS_GRAD_RECOMPUTE = 8 } kt_op;
+/* Element types and operation codes travel as plain 32-bit integers (like kt_status): a value outside
+ * the lists below is an argument error the library reports, never an invalid enumeration value. */
+typedef int32_t kt_dtype;
+enum { KT_F32 = 0, KT_BF16 = 1 };
+typedef int32_t kt_op;
+enum { KT_OP_LOSS_GRAD = 0, KT_OP_CAYLEY = 1, KT_OP_FAKEQUANT = 2, KT_OP_POOLED_LOSS_GRAD = 3,
+       KT_OP_QUANT_METRICS = 4, KT_OP_FUSE_ROTATION = 5,
+       KT_OP_SENSITIVITY = 6, KT_OP_LOSS_GRAD_RECOMPUTE = 7,
+       KT_OP_POOLED_LOSS_GRAD_RECOMPUTE = 8 };
 
 /* Library version (major*10000 + minor*100 + patch). Host call. */
 int32_t kt_version(void);
