@@ -907,7 +907,7 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
       return (unsigned)(32 * g0 + __builtin_ctzll(nz3));
     };
     unsigned kk = (unsigned)k, bin, cum, cnt;
-    // round 1, bits 30..20: every value of the row counts
+    // first digit, bits 30..20: every value of the row counts
     clear_hist();
 #pragma unroll
     for (int c = 0; c < NV4; ++c) {
@@ -920,7 +920,7 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
     pick(kk, bin, cum, cnt);
     const unsigned p11 = bin;
     kk -= cum;
-    // round 2, bits 19..9 of the values whose bits 30..20 equal p11
+    // second digit, bits 19..9 of the values whose bits 30..20 equal p11
     clear_hist();
 #pragma unroll
     for (int c = 0; c < NV4; ++c) {
@@ -940,7 +940,7 @@ __global__ __launch_bounds__(256, (NV4 <= 4 ? 4 : NV4 <= 16 ? 3 : 2)) void quant
     pick(kk, bin, cum, cnt);
     const unsigned p22 = (p11 << 11) | bin;
     kk -= cum;
-    // round 3, bits 8..0 of the values whose bits 30..9 equal p22; the same pass finds the smallest value
+    // third digit, bits 8..0 of the values whose bits 30..9 equal p22; the same pass finds the smallest value
     // beyond that group: u - base wraps to >= 2^31 for every u < base = (p22 + 1) 2^9 <= 2^31
     clear_hist();
     const unsigned base = (p22 + 1u) << 9;
