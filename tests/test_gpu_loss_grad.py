@@ -218,3 +218,26 @@ def test_fused_d128_batched_with_row_stride():
     R = torch.stack([ktgen.random_orthogonal(d, seed=30 + b) for b in range(batch)])
     o = oracle_loss_grad(X.cpu().contiguous(), R)
     check_loss_grad(gpu_loss_grad(X, R), o, TOL_BF16)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_output_that_is_only_four_byte_aligned(dtype):
+    """dR is fp32 and needs no more than its own alignment: a dR that starts 4 bytes into a buffer takes the
+    4-byte form of the store epilogue and must give the same bits as an aligned one (which takes the 16-byte form).
+    256 problems of d = 256: enough output tiles that the contraction is not split, so dR leaves the GEMM's
+    epilogue directly; the same call with one problem goes through the split partial sums and their reduction."""
+    d, n = 256, 200
+    for batch in (256, 1):
+        X = torch.stack([ktgen.make_x(n, d, seed=11 + b, outlier_cols=4, outlier_scale=30.0, dtype=dtype)
+                         for b in range(batch)]).cuda()
+        R = ktgen.random_orthogonal(d, seed=11).unsqueeze(0).repeat(batch, 1, 1).cuda()
+        aligned = torch.empty((batch, d, d), device="cuda")
+        buf = torch.zeros(batch * d * d + 8, device="cuda")
+        shifted = buf[1:1 + batch * d * d].view(batch, d, d)
+        assert shifted.data_ptr() % 16 == 4
+        kt.kt_kurtosis_loss_grad(X, R, dR=aligned)
+        kt.kt_kurtosis_loss_grad(X, R, dR=shifted)
+        torch.cuda.synchronize()
+        assert torch.equal(aligned, shifted), batch
+        assert torch.isfinite(aligned).all() and float(aligned.abs().max()) > 0
+        assert buf[0].item() == 0.0 and float(buf[1 + batch * d * d:].abs().max()) == 0.0   # nothing written outside
