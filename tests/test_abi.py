@@ -164,3 +164,19 @@ def test_static_scratch_entry_rejects_what_does_not_fit_before_touching_a_device
     assert L.kt_cayley_step_static(None, fake, None, 1, 256, 0.01, None, None, None) == 1
     assert L.kt_cayley_step_static(fake, fake, None, 1, 200, 0.01, None, None, None) == 2
     assert L.kt_cayley_step_static(fake, fake, None, 1, 256, float("nan"), None, None, None) == 1
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    """The boundary is a C ABI: include/kt.h must be valid C99 on its own (no C++-isms, no torch types)."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_kt.c"
+    src.write_text('#include "kt.h"\n'
+                   "int main(void) { kt_dtype t = KT_BF16; kt_op o = KT_OP_CAYLEY; kt_status s = KT_OK;\n"
+                   "  return (int)t + (int)o + (int)s == 2 ? 0 : 1; }\n")
+    res = subprocess.run([cc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                          "-c", str(src), "-o", str(tmp_path / "use_kt.o")], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
