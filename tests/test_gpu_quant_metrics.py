@@ -137,3 +137,46 @@ def test_without_y_the_rows_pass_through_a_bounded_staging_slice(n, d, batch):
         assert np.array_equal(outs[1]["amax"][b, ix].cpu().numpy(), o["amax"])
         assert np.allclose(outs[1]["err_sym"][b, ix].cpu().numpy(), o["err_sym"], rtol=2e-6, atol=0)
         assert np.allclose(outs[1]["err_asym"][b, ix].cpu().numpy(), o["err_asym"], rtol=2e-6, atol=0)
+
+
+@pytest.mark.parametrize("d", [128, 384, 1024, 4096])
+@pytest.mark.parametrize("q", [0.5, 0.98, 0.999, 1.0 / 3.0])
+def test_quantile_select_on_crafted_rows(d, q):
+    """The clipping threshold is an order statistic found by a radix select on bit patterns: it must be BIT-EXACT
+    on rows built to sit on the select's seams.  With the identity rotation and fp32 activations Y = X exactly,
+    so each row can be crafted bit by bit: all values equal; two distinct values; values that differ only in their
+    lowest 9 bits, or only above them; runs of consecutive bit patterns that straddle the 2^9 and 2^20 digit
+    boundaries; zeros, signed zeros and tiny values; one huge value; many copies of the order statistic itself."""
+    g = torch.Generator().manual_seed(d * 1000 + int(q * 1000))
+    base = torch.tensor(0x3F7FFE00, dtype=torch.int32)          # just below 1.0: patterns cross 0x3F800000
+    rows = []
+    rows.append(torch.full((d,), 0.37))                                                    # all equal
+    rows.append(torch.where(torch.rand(d, generator=g) < 0.5, torch.tensor(0.25), torch.tensor(-2.5)))   # two values
+    rows.append((base + torch.randint(0, 512, (d,), generator=g, dtype=torch.int32)).view(torch.float32))  # low 9 bits only
+    rows.append((base + 512 * torch.randint(0, 2048, (d,), generator=g, dtype=torch.int32)).view(torch.float32))  # bits 9..19 only
+    rows.append((base + torch.arange(d, dtype=torch.int32)).view(torch.float32))          # consecutive patterns over a 2^9 seam
+    rows.append((torch.tensor(0x3F0FFF00, dtype=torch.int32) + 37 * torch.arange(d, dtype=torch.int32)).view(torch.float32))  # over a 2^20 seam
+    z = torch.zeros(d)
+    z[::3] = -0.0
+    z[1::7] = 1e-30                                                                        # tiny values (1 / scale stays finite)
+    z[5] = 3.0
+    rows.append(z)
+    h = torch.randn(d, generator=g)
+    h[d // 2] = 1e15                                                                       # one huge value
+    rows.append(h)
+    t = torch.randn(d, generator=g)
+    k = int(np.floor(float(np.float32(q)) * (d - 1)))
+    srt = t.abs().sort().values
+    t[t.abs() >= srt[k]] = float(srt[k])                                                   # everything from rank k up is one value
+    rows.append(t)
+    rows.append(torch.randn(d, generator=g) * torch.exp(3 * torch.randn(d, generator=g)))  # wide dynamic range
+    X = torch.stack(rows)
+    sign = torch.where(torch.rand(X.shape, generator=g) < 0.5, -1.0, 1.0)
+    X = (X * sign).unsqueeze(0)
+    q = float(np.float32(q))   # the boundary takes the quantile as fp32: both sides get that value
+    gq = _gpu(X, torch.eye(d).unsqueeze(0), q)
+    o = oracle.quant_metrics(ktgen.to_f64(X[0]), np.eye(d), q)
+    assert np.array_equal(gq["threshold"][0], o["thr"]), (gq["threshold"][0], o["thr"])
+    assert np.array_equal(gq["amax"][0], o["amax"])
+    assert np.allclose(gq["err_sym"][0], o["err_sym"], rtol=2e-6, atol=1e-38)
+    assert np.allclose(gq["err_asym"][0], o["err_asym"], rtol=2e-6, atol=1e-38)
