@@ -194,7 +194,8 @@ __global__ __launch_bounds__(256) void finalize_rows_kernel(const floatx4* __res
   if (threadIdx.x == 0) loss_part[(int64_t)batch * gridDim.x + blockIdx.x] = s;
 }
 
-// dL/dY from a kept Y: GT[i] = grad_value(YT[i], coef of i's token) for every entry of the token-minor
+// dL/dY (chain rule through the kurtosis of Eq. 3; coefficients from finalize_rows_kernel) from a kept Y:
+// GT[i] = grad_value(YT[i], coef of i's token) for every entry of the token-minor
 // layout that EpiMomentsKeep / EpiGrad write (rows = features, blocks of tb tokens, tokens permuted inside
 // groups of 128: position 4 j + k of a group holds token j + 32 k).  A half wave takes one group of 128
 // positions (16 bytes of YT per lane), its four tokens' coefficients stay in registers while it walks

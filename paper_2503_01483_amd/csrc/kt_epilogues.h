@@ -145,7 +145,7 @@ struct EpiGrad : EpiBase {
   }
 };
 
-// ---- forward pass that also keeps Y: the moments of EpiMoments, and the fp32 accumulators written
+// ---- forward pass that also keeps Y = X R ("Learning the Rotations"): the moments of EpiMoments (Eq. 3), and the fp32 accumulators written
 // in the layout of GT above (features on the rows, tokens permuted inside groups of 128, blocks of tb
 // tokens): one 16-byte store per lane and feature.  grad_from_y_kernel then turns YT into GT entry by
 // entry, which replaces the recompute GEMM of the backward pass (same accumulators, same arithmetic: the
